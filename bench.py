@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X tree-verification step (one GPU).
+
+A step = tree_verify_attn + lmhead_softmax_cfg + cascade_accept + select_path over one batch of
+synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+The large read-only inputs (LM-head matrix, KV cache) are rotated over several independent copies
+so that consecutive steps cannot be served from the 256 MB Infinity Cache: in a real decode loop a
+whole model's weights stream between two verification steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_bytes_lmhead(inp) -> int:
+    """W once + hidden states in + mixed logits out (the projection kernel's own traffic)."""
+    rows = inp.n_nodes * (2 if inp.h_uncond is not None else 1)
+    e = 2 if inp.dtype == "bf16" else 4
+    return inp.vocab * inp.hidden * e + rows * inp.hidden * e + inp.n_nodes * inp.vocab * 4
+
+
+def algorithmic_flops_lmhead(inp) -> int:
+    rows = inp.n_nodes * (2 if inp.h_uncond is not None else 1)
+    return 2 * rows * inp.hidden * inp.vocab
+
+
+def algorithmic_bytes_attn(inp) -> int:
+    """K and V of prefix + tree once per (row, kv head); Q in and O out."""
+    e = 2 if inp.dtype == "bf16" else 4
+    total = 0
+    for s in range(inp.n_rows):
+        T = int(inp.row_node_off[s + 1] - inp.row_node_off[s])
+        total += inp.n_kv_heads * (int(inp.prefix_len[s]) + T) * inp.head_dim * 2 * e
+        total += T * inp.n_heads * inp.head_dim * 2 * e
+    return total
+
+
+def cpu_baseline(inp, budget_s: float = 12.0):
+    """The CPU checker, as it stands, on the same workload; whole steps until the budget is used."""
+    from oracle import verify_oracle as vo
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    n, t0 = 0, time.perf_counter()
+    while True:
+        vo.verify_step(inp)
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or n >= 20:
+            break
+    return {"value": n / el, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n} whole step(s) of the same workload (numpy float64; BLAS threads = cores), {el:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", type=int, default=1, help="index into the five configurations (default 1: Janus-Pro-7B-shaped)")
+    ap.add_argument("--copies", type=int, default=4, help="independent copies of W / KV rotated between steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2605_07230_amd import binding, workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the verification path has no CPU fallback", file=sys.stderr)
+        return 3
+    binding.load_library()
+    torch.cuda.set_device(0)
+
+    inp = wl.make_config(args.workload, args.seed)
+    ds = binding.DeviceStep(inp)
+    copies = max(1, args.copies)
+    ws = [ds.w] + [ds.w.clone() for _ in range(copies - 1)]
+    kcs = [ds.k_cache] + [ds.k_cache.clone() for _ in range(copies - 1)]
+    vcs = [ds.v_cache] + [ds.v_cache.clone() for _ in range(copies - 1)]
+
+    def step(i: int) -> None:
+        j = i % copies
+        ds.k_cache, ds.v_cache = kcs[j], vcs[j]
+        ds.step(w=ws[j])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    assert ds.ctx.device_status() == binding.OK
+
+    # second pass with HIP events around every kernel launch (on the library's stream)
+    ds.ctx.set_kernel_timing(True)
+    n_timed = min(args.steps, 2000)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(n_timed):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step_events = (time.perf_counter() - t1) * 1e3 / n_timed
+    names = ["attn", "attn_merge", "lmhead", "row_stats", "accept", "select"]
+    kernel_us = {}
+    for kid, name in enumerate(names):
+        ms, n = ds.ctx.read_kernel_timing(kid)
+        if n:
+            kernel_us[name] = ms * 1e3 / n
+    ds.ctx.set_kernel_timing(False)
+
+    # roofline of the dominant kernel
+    dominant = max(kernel_us, key=kernel_us.get)
+    if dominant == "lmhead":
+        rows = inp.n_nodes * (2 if inp.h_uncond is not None else 1)
+        if rows >= 300:
+            flops = algorithmic_flops_lmhead(inp)
+            ach = flops / (kernel_us["lmhead"] * 1e-6) / 1e12
+            roof = {"kernel": "lmhead_bf16_kernel", "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+        else:
+            nbytes = algorithmic_bytes_lmhead(inp)
+            ach = nbytes / (kernel_us["lmhead"] * 1e-6) / 1e9
+            roof = {"kernel": "lmhead_bf16_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": nbytes}
+    else:
+        nbytes = algorithmic_bytes_attn(inp)
+        us = kernel_us.get("attn", 0.0) + kernel_us.get("attn_merge", 0.0)
+        ach = nbytes / (us * 1e-6) / 1e9
+        roof = {"kernel": "attn_bf16_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": nbytes}
+    roof["avg_launch_us"] = kernel_us[dominant if dominant != "attn_merge" else "attn"]
+
+    out = {
+        "metric": "tree_verify_steps_per_s", "value": args.steps / elapsed, "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": inp.dtype, "data": "synthetic",
+        "config": {"workload": inp.name, "rows": inp.n_rows, "prompts": inp.n_prompts, "tree_nodes": inp.n_nodes,
+                   "prefix_len": int(inp.prefix_len.max()), "heads": inp.n_heads, "head_dim": inp.head_dim,
+                   "hidden": inp.hidden, "vocab": inp.vocab, "cfg_scale": inp.cfg_scale, "top_k": inp.top_k,
+                   "input_copies_rotated": copies},
+        "tree_nodes_per_s": inp.n_nodes * args.steps / elapsed,
+        "ms_per_step_with_events": ms_per_step_events,
+        "kernel_us": kernel_us,
+        "attn_hbm_frac": (algorithmic_bytes_attn(inp) / ((kernel_us.get("attn", 0) + kernel_us.get("attn_merge", 0)) * 1e-6) / 1e9
+                          / HBM_PEAK_GBS) if kernel_us.get("attn") else None,
+        "accept_len": ds.accept_len.cpu().tolist(),
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

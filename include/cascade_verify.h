@@ -1,0 +1,244 @@
+/*
+ * cascade_verify.h — C ABI of the MI355X (gfx950) tree-verification step of CASCADE
+ * speculative image decoding.
+ *
+ * One verification step = four calls, in this order, on one HIP stream:
+ *
+ *   tree_verify_attn    target attention of the drafted token tree against the prefix KV cache
+ *   lmhead_softmax_cfg  final projection + classifier-free-guidance mix + top-k + softmax statistics
+ *   cascade_accept      per-node quantities of the relaxed acceptance rule (Eq. 1, Eq. 2, Eq. 3)
+ *   select_path         the walk of Alg. 2 (budget, acceptance test) and the correction step of Alg. 1
+ *
+ * General conventions
+ * -------------------
+ *  - C99, no C++ types.  Every pointer inside an args struct is a DEVICE pointer unless its
+ *    comment says HOST.  The args structs themselves and the ctx handle live on the host.
+ *  - Ownership: the caller owns every buffer.  The library borrows them until the ctx stream has
+ *    run the enqueued work.  Outputs are caller-allocated.  The library allocates device memory
+ *    only inside cascade_create (one workspace, freed by cascade_destroy).
+ *  - Asynchrony: every compute call enqueues kernels on the ctx stream and returns; it never
+ *    synchronises the device.
+ *  - Errors: 0 = CASCADE_OK, negative = cascade_status.  Errors detectable from host-visible
+ *    arguments (null pointers, shapes, limits, dtype) are reported before anything is enqueued and
+ *    leave outputs untouched.  HIP runtime failures give CASCADE_EHIP.  Preconditions on device
+ *    arrays (below) cannot be seen by the host; kernels never read or write out of bounds because
+ *    of them, they record a flag that cascade_device_status returns.
+ *  - Packing: a *prompt* owns one token tree.  node_off[b]..node_off[b+1] are prompt b's nodes in
+ *    the packed arrays; parent[] holds indices LOCAL to the tree; node 0 of each tree is its root
+ *    (the last token already emitted), parent == -1, and parent[i] < i for i > 0.  Siblings are
+ *    tried in ascending node index.  A node has at most CASCADE_MAX_WIDTH children.
+ *  - With classifier-free guidance a prompt has two attention rows (conditional, unconditional)
+ *    sharing the tree; attention is packed per ROW, the other three calls per PROMPT.
+ */
+#ifndef CASCADE_VERIFY_H
+#define CASCADE_VERIFY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cascade_ctx cascade_ctx;   /* opaque; owns the workspace; bound to one HIP stream */
+
+typedef enum {
+  CASCADE_OK = 0,
+  CASCADE_EINVAL = -1,    /* null pointer, negative size, NaN threshold, bad enum */
+  CASCADE_ESHAPE = -2,    /* a size exceeds the ctx limits or breaks a divisibility rule */
+  CASCADE_EDTYPE = -3,    /* dtype not supported by this call */
+  CASCADE_ENOMEM = -4,    /* workspace allocation failed (cascade_create only) */
+  CASCADE_EHIP = -5,      /* HIP runtime error; text via cascade_strerror(CASCADE_EHIP) */
+  CASCADE_ETREE = -6      /* a device-side precondition was violated (cascade_device_status) */
+} cascade_status;
+
+typedef enum { CASCADE_F32 = 0, CASCADE_BF16 = 1 } cascade_dtype;
+
+/* SEQUENTIAL is Alg. 2 as printed (siblings tried in order, first accepted child descends).
+ * LONGEST simulates the same rule along every root-to-leaf path on its own and keeps the path
+ * with the longest accepted prefix (ties: smallest leaf index). */
+typedef enum { CASCADE_WALK_SEQUENTIAL = 0, CASCADE_WALK_LONGEST = 1 } cascade_walk_mode;
+
+#define CASCADE_MAX_WIDTH 64      /* children per node */
+#define CASCADE_MAX_TREE 1024     /* nodes per tree */
+#define CASCADE_MAX_DEPTH 64      /* levels below the root */
+#define CASCADE_MAX_VOCAB 65536   /* image(+text) vocabulary entries */
+
+/* Upper bounds used to size the workspace.  All HOST values. */
+typedef struct {
+  int32_t max_rows;            /* attention rows S (2 per prompt with guidance) */
+  int32_t max_nodes_total;     /* packed nodes over all rows */
+  int32_t max_nodes_per_tree;  /* <= CASCADE_MAX_TREE */
+  int32_t max_prefix;          /* prefix KV positions per row */
+  int32_t n_heads;             /* query heads */
+  int32_t head_dim;            /* 64 or 128 for bf16; any multiple of 4 up to 256 for f32 */
+  int32_t hidden;
+  int32_t vocab;               /* <= CASCADE_MAX_VOCAB */
+} cascade_limits;
+
+/* Allocates the workspace on the current device and binds the ctx to hip_stream (a hipStream_t
+ * passed as void*; NULL = the default stream).  Returns CASCADE_OK and stores the handle, or a
+ * negative status and stores NULL. */
+int cascade_create(cascade_ctx** out, const cascade_limits* limits, void* hip_stream);
+int cascade_destroy(cascade_ctx* ctx);
+/* Static text for a status; for CASCADE_EHIP the text of the last HIP error seen by this thread. */
+const char* cascade_strerror(int status);
+/* Synchronises the ctx stream, returns CASCADE_OK or CASCADE_ETREE if any kernel since the last
+ * call met a violated precondition (parent[i] >= i, more than CASCADE_MAX_WIDTH children, token
+ * outside [0, vocab), tree deeper than max_depth), and clears the flag. */
+int cascade_device_status(cascade_ctx* ctx);
+/* Bytes of device workspace the ctx holds (HOST query). */
+int64_t cascade_workspace_bytes(const cascade_ctx* ctx);
+
+/* Optional per-kernel timing, for benchmarks.  When enabled, every launch of the kernels below is
+ * bracketed by two HIP events recorded on the ctx stream (at most 2048 launches per kernel are
+ * kept between reads; later ones are not timed).  cascade_read_kernel_timing synchronises the
+ * stream, returns the summed elapsed milliseconds and the number of timed launches of one kernel,
+ * and resets that kernel's counter.  Timing is off by default and costs nothing when off. */
+typedef enum {
+  CASCADE_K_ATTN = 0,        /* tree attention main kernel */
+  CASCADE_K_ATTN_MERGE = 1,  /* split-KV merge */
+  CASCADE_K_LMHEAD = 2,      /* projection + guidance mix */
+  CASCADE_K_ROW_STATS = 3,   /* row max / top-k threshold / log-sum-exp */
+  CASCADE_K_ACCEPT = 4,
+  CASCADE_K_SELECT = 5,
+  CASCADE_K_COUNT = 6
+} cascade_kernel_id;
+int cascade_set_kernel_timing(cascade_ctx* ctx, int enable);
+int cascade_read_kernel_timing(cascade_ctx* ctx, int kernel_id, double* total_ms, int32_t* launches);
+
+/* ---------------------------------------------------------------------------------------------
+ * tree_verify_attn — the target model's parallel pass over the drafted tree, one decoder layer's
+ * attention (Preliminaries: the target evaluates all draft tokens in one parallel forward pass,
+ * each conditioned on the prefix plus its own draft path; tree decoding with a tree mask).
+ *
+ * For row s, query head g (kv head g / (n_heads / n_kv_heads)) and node i of the row:
+ *     J   = { prefix positions 0 .. prefix_len[s]-1 }  U  { tree nodes a : a ancestor of i, or a == i }
+ *     out = sum_{j in J} softmax_j( scale * <q_i, k_j> ) * v_j
+ * The ancestor mask is derived from parent[] on chip; it is never materialised in HBM.
+ *
+ * Layouts (element type = dtype; strides in ELEMENTS):
+ *     q, out           [N, n_heads, head_dim]       contiguous, N = node_off[n_rows]
+ *     k_tree, v_tree   [N, n_kv_heads, head_dim]    contiguous
+ *     k_cache, v_cache element (s, kvh, pos, d) at s*cache_stride_row + kvh*cache_stride_head
+ *                      + pos*cache_stride_pos + d   (d contiguous; strides multiples of 8 for bf16)
+ *     lse              [N, n_heads] float32, log-sum-exp of the scaled scores over J; may be NULL
+ * out is written in dtype (bf16: round to nearest even); accumulation and softmax are float32.
+ */
+typedef struct {
+  int32_t n_rows;
+  const int32_t* node_off;    /* [n_rows+1] DEVICE */
+  const int32_t* parent;      /* [N] DEVICE, local indices */
+  const int32_t* prefix_len;  /* [n_rows] DEVICE */
+  int32_t n_nodes_total;      /* HOST copy of node_off[n_rows] */
+  int32_t max_nodes_per_tree; /* HOST upper bound on any row's node count */
+  int32_t max_prefix_len;     /* HOST upper bound on any prefix_len[s] */
+  cascade_dtype dtype;
+  int32_t n_heads, n_kv_heads, head_dim;
+  float scale;                /* 0 => 1/sqrt(head_dim) */
+  const void *q, *k_tree, *v_tree;
+  const void *k_cache, *v_cache;
+  int64_t cache_stride_row, cache_stride_head, cache_stride_pos;
+  void* out;
+  float* lse;                 /* nullable */
+} tree_attn_args;
+int tree_verify_attn(cascade_ctx* ctx, const tree_attn_args* args);
+
+/* ---------------------------------------------------------------------------------------------
+ * lmhead_softmax_cfg — final projection at every tree node (Sec. 4.2: the O(hV) projection is
+ * the dominant term), guidance mix, temperature, top-k and softmax statistics (App.
+ * "Configuration Details": guidance scale 3 or 5, temperature 1, top-k 2000, top-p 1).
+ *
+ *     l_c = h_cond W^T,  l_u = h_uncond W^T            (float32 accumulation)
+ *     g   = l_u + cfg_scale * (l_c - l_u)              (h_uncond == NULL:  g = l_c)
+ *     g   = g / temperature
+ *     row_thr = top_k-th largest g of the row          (top_k <= 0 or >= vocab: -inf, no filter)
+ *     row_max = max_v g,  row_lse = log sum_{g_v >= row_thr} exp(g_v)
+ * The node's target distribution is  q(v) = g_v >= row_thr ? exp(g_v - row_lse) : 0 ; it is not
+ * materialised.  Raw conditional / unconditional logits are never written.
+ *
+ *     h_cond, h_uncond [n_nodes, hidden] dtype, contiguous;  w [vocab, hidden] dtype, contiguous
+ *     logits [n_nodes, vocab] float32 (mixed, after temperature, before the filter)
+ *     row_max, row_thr, row_lse [n_nodes] float32
+ * bf16: hidden must be a multiple of 64 and vocab a multiple of 64.
+ */
+typedef struct {
+  cascade_dtype dtype;
+  int32_t n_nodes, hidden, vocab;
+  const void* h_cond;
+  const void* h_uncond;       /* nullable => no guidance */
+  const void* w;
+  float cfg_scale, temperature;
+  int32_t top_k;
+  float* logits;
+  float *row_max, *row_thr, *row_lse;
+} lmhead_args;
+int lmhead_softmax_cfg(cascade_ctx* ctx, const lmhead_args* args);
+
+/* ---------------------------------------------------------------------------------------------
+ * cascade_accept — what the relaxed acceptance rule needs at every non-root node a with parent p
+ * (Sec. 4.1 cosine similarity of target hidden states; Eq. 1 interchangeable set; Eq. 2
+ * convergence set; Eq. 3 aggregated mass).  Q = the distribution of p (the one that verifies a):
+ *
+ *     q_tok[a]  = Q[token[a]]
+ *     I_a = { siblings b != a : cos(F_a, F_b) >= tau_pos },  n_int[a]  = |I_a|
+ *     C_a = { children b of a : cos(F_a, F_b) >= tau_seq },  n_conv[a] = |C_a|
+ *     m_int[a]  = sum of Q[t] over distinct t in tokens(I_a) \ {token[a]}
+ *     m_conv[a] = sum of Q[t] over distinct t in tokens(C_a) \ {token[a]} \ tokens(I_a)
+ *     cos_parent[a] = cos(F_p, F_a)
+ * F = rows of h_cond (the conditional row's final hidden state, the LM-head input).  cos is 0 when
+ * a norm is 0.  A threshold > 1 disables that relaxation.  Root entries are written as 0.
+ * Dot products and norms accumulate in float32.
+ *
+ *     node_off [n_prompts+1], parent/token [N] int32;  h_cond [N, hidden] h_dtype
+ *     logits [N, vocab] float32 and row_thr/row_lse [N] as written by lmhead_softmax_cfg
+ *     outputs [N]: q_tok, m_int, m_conv, cos_parent float32;  n_int, n_conv int32
+ */
+typedef struct {
+  cascade_dtype h_dtype;
+  int32_t n_prompts, n_nodes_total, hidden, vocab;
+  const int32_t *node_off, *parent, *token;
+  const void* h_cond;
+  const float *logits, *row_thr, *row_lse;
+  float tau_pos, tau_seq;
+  float *q_tok, *m_int, *m_conv, *cos_parent;
+  int32_t *n_int, *n_conv;
+} accept_args;
+int cascade_accept(cascade_ctx* ctx, const accept_args* args);
+
+/* ---------------------------------------------------------------------------------------------
+ * select_path — Alg. 2's walk over the scalars of cascade_accept, then Alg. 1's correction step.
+ *
+ * SEQUENTIAL, per prompt:  cur = root, tvd = 0; at each level try the children a of cur in
+ * ascending index:  q = q_tok[a];  if n_int[a] > 0 and tvd + m_int[a] <= eps_tvd: q += m_int[a],
+ * tvd += m_int[a];  the same for (n_conv, m_conv);  a is accepted iff u[a]*draft_prob[a] < q
+ * (Alg. 1's r < min(1, q/p) with 0 <= r < 1).  The first accepted child becomes cur; a level with
+ * no accepted child, or a leaf, ends the walk.  The last token is drawn from the distribution of
+ * cur with the tokens of the children rejected at that last level removed: the smallest v with
+ * cumulative mass > u_bonus[b] * remaining mass (vocabulary order).
+ * All compares and sums in float32.
+ *
+ *     draft_prob [N] float32 (NULL => 1), u [N] float32 in [0,1), u_bonus [n_prompts] in [0,1)
+ *     accept_len [n_prompts]; path_nodes [n_prompts, max_depth] local indices, -1 padded;
+ *     emitted [n_prompts, max_depth+1]: accepted draft tokens, then the last token, -1 padded;
+ *     terminal [n_prompts] local index of cur at the end; tvd_used [n_prompts] float32
+ */
+typedef struct {
+  int32_t n_prompts, n_nodes_total, vocab, max_depth;
+  cascade_walk_mode mode;
+  const int32_t *node_off, *parent, *token;
+  const float *q_tok, *m_int, *m_conv;
+  const int32_t *n_int, *n_conv;
+  const float* draft_prob;    /* nullable */
+  const float* u;
+  const float* u_bonus;
+  float eps_tvd;
+  const float *logits, *row_thr, *row_lse;
+  int32_t *accept_len, *path_nodes, *emitted, *terminal;
+  float* tvd_used;
+} select_args;
+int select_path(cascade_ctx* ctx, const select_args* args);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CASCADE_VERIFY_H */

@@ -1,0 +1,291 @@
+"""ctypes binding of libcascade_verify.so: argument marshalling only.
+
+Every step of the verification path runs in the HIP library.  torch supplies device
+buffers and the stream; nothing here computes.  The four compute functions carry the
+names of the C entry points.  If the library cannot be loaded this module raises —
+there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcascade_verify.so")
+
+F32, BF16 = 0, 1
+WALK_SEQUENTIAL, WALK_LONGEST = 0, 1
+K_ATTN, K_ATTN_MERGE, K_LMHEAD, K_ROW_STATS, K_ACCEPT, K_SELECT = range(6)
+OK, EINVAL, ESHAPE, EDTYPE, ENOMEM, EHIP, ETREE = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = ["cascade_create", "cascade_destroy", "cascade_strerror", "cascade_device_status", "cascade_workspace_bytes",
+           "cascade_set_kernel_timing", "cascade_read_kernel_timing", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path"]
+
+_vp, _i32, _i64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+
+
+class cascade_limits(C.Structure):
+    _fields_ = [("max_rows", _i32), ("max_nodes_total", _i32), ("max_nodes_per_tree", _i32), ("max_prefix", _i32),
+                ("n_heads", _i32), ("head_dim", _i32), ("hidden", _i32), ("vocab", _i32)]
+
+
+class tree_attn_args(C.Structure):
+    _fields_ = [("n_rows", _i32), ("node_off", _vp), ("parent", _vp), ("prefix_len", _vp), ("n_nodes_total", _i32),
+                ("max_nodes_per_tree", _i32), ("max_prefix_len", _i32), ("dtype", C.c_int), ("n_heads", _i32),
+                ("n_kv_heads", _i32), ("head_dim", _i32), ("scale", _f32), ("q", _vp), ("k_tree", _vp), ("v_tree", _vp),
+                ("k_cache", _vp), ("v_cache", _vp), ("cache_stride_row", _i64), ("cache_stride_head", _i64),
+                ("cache_stride_pos", _i64), ("out", _vp), ("lse", _vp)]
+
+
+class lmhead_args(C.Structure):
+    _fields_ = [("dtype", C.c_int), ("n_nodes", _i32), ("hidden", _i32), ("vocab", _i32), ("h_cond", _vp),
+                ("h_uncond", _vp), ("w", _vp), ("cfg_scale", _f32), ("temperature", _f32), ("top_k", _i32),
+                ("logits", _vp), ("row_max", _vp), ("row_thr", _vp), ("row_lse", _vp)]
+
+
+class accept_args(C.Structure):
+    _fields_ = [("h_dtype", C.c_int), ("n_prompts", _i32), ("n_nodes_total", _i32), ("hidden", _i32), ("vocab", _i32),
+                ("node_off", _vp), ("parent", _vp), ("token", _vp), ("h_cond", _vp), ("logits", _vp), ("row_thr", _vp),
+                ("row_lse", _vp), ("tau_pos", _f32), ("tau_seq", _f32), ("q_tok", _vp), ("m_int", _vp), ("m_conv", _vp),
+                ("cos_parent", _vp), ("n_int", _vp), ("n_conv", _vp)]
+
+
+class select_args(C.Structure):
+    _fields_ = [("n_prompts", _i32), ("n_nodes_total", _i32), ("vocab", _i32), ("max_depth", _i32), ("mode", C.c_int),
+                ("node_off", _vp), ("parent", _vp), ("token", _vp), ("q_tok", _vp), ("m_int", _vp), ("m_conv", _vp),
+                ("n_int", _vp), ("n_conv", _vp), ("draft_prob", _vp), ("u", _vp), ("u_bonus", _vp), ("eps_tvd", _f32),
+                ("logits", _vp), ("row_thr", _vp), ("row_lse", _vp), ("accept_len", _vp), ("path_nodes", _vp),
+                ("emitted", _vp), ("terminal", _vp), ("tvd_used", _vp)]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load the HIP library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_07230_amd.build` "
+                           "(the verification path has no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    lib.cascade_create.argtypes = [C.POINTER(_vp), C.POINTER(cascade_limits), _vp]
+    lib.cascade_create.restype = C.c_int
+    lib.cascade_destroy.argtypes = [_vp]
+    lib.cascade_destroy.restype = C.c_int
+    lib.cascade_strerror.argtypes = [C.c_int]
+    lib.cascade_strerror.restype = C.c_char_p
+    lib.cascade_device_status.argtypes = [_vp]
+    lib.cascade_device_status.restype = C.c_int
+    lib.cascade_workspace_bytes.argtypes = [_vp]
+    lib.cascade_workspace_bytes.restype = C.c_int64
+    lib.cascade_set_kernel_timing.argtypes = [_vp, C.c_int]
+    lib.cascade_set_kernel_timing.restype = C.c_int
+    lib.cascade_read_kernel_timing.argtypes = [_vp, C.c_int, C.POINTER(C.c_double), C.POINTER(_i32)]
+    lib.cascade_read_kernel_timing.restype = C.c_int
+    for name, st in (("tree_verify_attn", tree_attn_args), ("lmhead_softmax_cfg", lmhead_args),
+                     ("cascade_accept", accept_args), ("select_path", select_args)):
+        fn = getattr(lib, name)
+        fn.argtypes = [_vp, C.POINTER(st)]
+        fn.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+class CascadeError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"cascade status {status}: {load_library().cascade_strerror(status).decode()}")
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise CascadeError(status)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+class Context:
+    """Owns a cascade_ctx bound to a torch stream."""
+
+    def __init__(self, *, max_rows, max_nodes_total, max_nodes_per_tree, max_prefix, n_heads, head_dim, hidden, vocab,
+                 stream: Optional[torch.cuda.Stream] = None):
+        self.lib = load_library()
+        self.limits = cascade_limits(max_rows, max_nodes_total, max_nodes_per_tree, max_prefix, n_heads, head_dim, hidden, vocab)
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        self.handle = _vp()
+        _check(self.lib.cascade_create(C.byref(self.handle), C.byref(self.limits), _vp(self.stream.cuda_stream)))
+
+    def close(self) -> None:
+        if self.handle:
+            self.lib.cascade_destroy(self.handle)
+            self.handle = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def device_status(self) -> int:
+        return self.lib.cascade_device_status(self.handle)
+
+    def workspace_bytes(self) -> int:
+        return int(self.lib.cascade_workspace_bytes(self.handle))
+
+    def set_kernel_timing(self, enable: bool) -> None:
+        _check(self.lib.cascade_set_kernel_timing(self.handle, int(enable)))
+
+    def read_kernel_timing(self, kernel_id: int):
+        """(total milliseconds, timed launches) of one kernel since the last read."""
+        ms, n = C.c_double(), _i32()
+        _check(self.lib.cascade_read_kernel_timing(self.handle, kernel_id, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
+
+def tree_verify_attn(ctx: Context, *, node_off, parent, prefix_len, q, k_tree, v_tree, k_cache, v_cache, out,
+                     lse=None, scale: float = 0.0, max_nodes_per_tree: int, max_prefix_len: int) -> None:
+    """q/out [N,Hq,D], k_tree/v_tree [N,Hkv,D], k_cache/v_cache [S,Hkv,P_cap,D] (last dim contiguous)."""
+    a = tree_attn_args()
+    a.n_rows = prefix_len.numel()
+    a.node_off, a.parent, a.prefix_len = _ptr(node_off), _ptr(parent), _ptr(prefix_len)
+    a.n_nodes_total = q.shape[0]
+    a.max_nodes_per_tree, a.max_prefix_len = max_nodes_per_tree, max_prefix_len
+    a.dtype = _dtype_code(q)
+    a.n_heads, a.n_kv_heads, a.head_dim = q.shape[1], k_tree.shape[1], q.shape[2]
+    a.scale = scale
+    a.q, a.k_tree, a.v_tree = _ptr(q), _ptr(k_tree), _ptr(v_tree)
+    a.k_cache, a.v_cache = _ptr(k_cache), _ptr(v_cache)
+    if k_cache is not None:
+        assert k_cache.stride() == v_cache.stride() and k_cache.stride(3) == 1
+        a.cache_stride_row, a.cache_stride_head, a.cache_stride_pos = k_cache.stride(0), k_cache.stride(1), k_cache.stride(2)
+    a.out, a.lse = _ptr(out), _ptr(lse)
+    _check(ctx.lib.tree_verify_attn(ctx.handle, C.byref(a)))
+
+
+def lmhead_softmax_cfg(ctx: Context, *, h_cond, h_uncond, w, cfg_scale, temperature, top_k, logits, row_max, row_thr, row_lse) -> None:
+    a = lmhead_args()
+    a.dtype = _dtype_code(w)
+    a.n_nodes, a.hidden, a.vocab = h_cond.shape[0], h_cond.shape[1], w.shape[0]
+    a.h_cond, a.h_uncond, a.w = _ptr(h_cond), _ptr(h_uncond), _ptr(w)
+    a.cfg_scale, a.temperature, a.top_k = cfg_scale, temperature, top_k
+    a.logits, a.row_max, a.row_thr, a.row_lse = _ptr(logits), _ptr(row_max), _ptr(row_thr), _ptr(row_lse)
+    _check(ctx.lib.lmhead_softmax_cfg(ctx.handle, C.byref(a)))
+
+
+def cascade_accept(ctx: Context, *, node_off, parent, token, h_cond, logits, row_thr, row_lse, tau_pos, tau_seq,
+                   q_tok, m_int, m_conv, cos_parent, n_int, n_conv) -> None:
+    a = accept_args()
+    a.h_dtype = _dtype_code(h_cond)
+    a.n_prompts, a.n_nodes_total, a.hidden, a.vocab = node_off.numel() - 1, h_cond.shape[0], h_cond.shape[1], logits.shape[1]
+    a.node_off, a.parent, a.token, a.h_cond = _ptr(node_off), _ptr(parent), _ptr(token), _ptr(h_cond)
+    a.logits, a.row_thr, a.row_lse = _ptr(logits), _ptr(row_thr), _ptr(row_lse)
+    a.tau_pos, a.tau_seq = tau_pos, tau_seq
+    a.q_tok, a.m_int, a.m_conv, a.cos_parent = _ptr(q_tok), _ptr(m_int), _ptr(m_conv), _ptr(cos_parent)
+    a.n_int, a.n_conv = _ptr(n_int), _ptr(n_conv)
+    _check(ctx.lib.cascade_accept(ctx.handle, C.byref(a)))
+
+
+def select_path(ctx: Context, *, node_off, parent, token, q_tok, m_int, m_conv, n_int, n_conv, draft_prob, u, u_bonus,
+                eps_tvd, logits, row_thr, row_lse, max_depth, mode, accept_len, path_nodes, emitted, terminal, tvd_used) -> None:
+    a = select_args()
+    a.n_prompts, a.n_nodes_total, a.vocab, a.max_depth, a.mode = node_off.numel() - 1, token.numel(), logits.shape[1], max_depth, mode
+    a.node_off, a.parent, a.token = _ptr(node_off), _ptr(parent), _ptr(token)
+    a.q_tok, a.m_int, a.m_conv, a.n_int, a.n_conv = _ptr(q_tok), _ptr(m_int), _ptr(m_conv), _ptr(n_int), _ptr(n_conv)
+    a.draft_prob, a.u, a.u_bonus, a.eps_tvd = _ptr(draft_prob), _ptr(u), _ptr(u_bonus), eps_tvd
+    a.logits, a.row_thr, a.row_lse = _ptr(logits), _ptr(row_thr), _ptr(row_lse)
+    a.accept_len, a.path_nodes, a.emitted = _ptr(accept_len), _ptr(path_nodes), _ptr(emitted)
+    a.terminal, a.tvd_used = _ptr(terminal), _ptr(tvd_used)
+    _check(ctx.lib.select_path(ctx.handle, C.byref(a)))
+
+
+# ------------------------------------------------------------------------------------------------
+# convenience: device buffers for a generated workload and one whole step (marshalling only)
+
+class DeviceStep:
+    """Uploads a workloads.VerifyInputs record and owns the output buffers of one step."""
+
+    def __init__(self, inp, device="cuda:0", stream: Optional[torch.cuda.Stream] = None):
+        self.inp = inp
+        dev = torch.device(device)
+        dt = torch.bfloat16 if inp.dtype == "bf16" else torch.float32
+
+        def up(x, dtype=None):
+            t = torch.from_numpy(x).to(dev)
+            return t.to(dtype) if dtype is not None else t
+
+        self.node_off, self.parent, self.token = up(inp.node_off), up(inp.parent), up(inp.token)
+        self.row_node_off, self.row_parent, self.prefix_len = up(inp.row_node_off), up(inp.row_parent), up(inp.prefix_len)
+        self.q, self.k_tree, self.v_tree = up(inp.q, dt), up(inp.k_tree, dt), up(inp.v_tree, dt)
+        self.k_cache, self.v_cache = up(inp.k_cache, dt), up(inp.v_cache, dt)
+        self.h_cond = up(inp.h_cond, dt)
+        self.h_uncond = up(inp.h_uncond, dt) if inp.h_uncond is not None else None
+        self.w = up(inp.w, dt)
+        self.draft_prob, self.u, self.u_bonus = up(inp.draft_prob), up(inp.u), up(inp.u_bonus)
+        N_a, N_c, B = inp.q.shape[0], inp.n_nodes, inp.n_prompts
+        self.max_depth = inp.max_depth
+        self.max_tree = int((inp.node_off[1:] - inp.node_off[:-1]).max())
+        f32, i32 = torch.float32, torch.int32
+        self.attn_out = torch.empty((N_a, inp.n_heads, inp.head_dim), dtype=dt, device=dev)
+        self.attn_lse = torch.empty((N_a, inp.n_heads), dtype=f32, device=dev)
+        self.logits = torch.empty((N_c, inp.vocab), dtype=f32, device=dev)
+        self.row_max, self.row_thr, self.row_lse = (torch.empty(N_c, dtype=f32, device=dev) for _ in range(3))
+        self.q_tok, self.m_int, self.m_conv, self.cos_parent = (torch.empty(N_c, dtype=f32, device=dev) for _ in range(4))
+        self.n_int, self.n_conv = (torch.empty(N_c, dtype=i32, device=dev) for _ in range(2))
+        self.accept_len = torch.empty(B, dtype=i32, device=dev)
+        self.path_nodes = torch.empty((B, max(self.max_depth, 1)), dtype=i32, device=dev)
+        self.emitted = torch.empty((B, self.max_depth + 1), dtype=i32, device=dev)
+        self.terminal = torch.empty(B, dtype=i32, device=dev)
+        self.tvd_used = torch.empty(B, dtype=f32, device=dev)
+        self.ctx = Context(max_rows=inp.n_rows, max_nodes_total=max(N_a, N_c), max_nodes_per_tree=self.max_tree,
+                           max_prefix=int(inp.prefix_len.max()), n_heads=inp.n_heads, head_dim=inp.head_dim,
+                           hidden=inp.hidden, vocab=inp.vocab, stream=stream)
+
+    def attn(self):
+        tree_verify_attn(self.ctx, node_off=self.row_node_off, parent=self.row_parent, prefix_len=self.prefix_len,
+                         q=self.q, k_tree=self.k_tree, v_tree=self.v_tree, k_cache=self.k_cache, v_cache=self.v_cache,
+                         out=self.attn_out, lse=self.attn_lse, max_nodes_per_tree=self.max_tree,
+                         max_prefix_len=int(self.inp.prefix_len.max()))
+
+    def lmhead(self, w=None):
+        lmhead_softmax_cfg(self.ctx, h_cond=self.h_cond, h_uncond=self.h_uncond, w=self.w if w is None else w,
+                           cfg_scale=self.inp.cfg_scale, temperature=self.inp.temperature, top_k=self.inp.top_k,
+                           logits=self.logits, row_max=self.row_max, row_thr=self.row_thr, row_lse=self.row_lse)
+
+    def accept(self, tau_pos=None, tau_seq=None):
+        cascade_accept(self.ctx, node_off=self.node_off, parent=self.parent, token=self.token, h_cond=self.h_cond,
+                       logits=self.logits, row_thr=self.row_thr, row_lse=self.row_lse,
+                       tau_pos=self.inp.tau_pos if tau_pos is None else tau_pos,
+                       tau_seq=self.inp.tau_seq if tau_seq is None else tau_seq,
+                       q_tok=self.q_tok, m_int=self.m_int, m_conv=self.m_conv, cos_parent=self.cos_parent,
+                       n_int=self.n_int, n_conv=self.n_conv)
+
+    def select(self, mode=WALK_SEQUENTIAL, eps_tvd=None):
+        select_path(self.ctx, node_off=self.node_off, parent=self.parent, token=self.token, q_tok=self.q_tok,
+                    m_int=self.m_int, m_conv=self.m_conv, n_int=self.n_int, n_conv=self.n_conv,
+                    draft_prob=self.draft_prob, u=self.u, u_bonus=self.u_bonus,
+                    eps_tvd=self.inp.eps_tvd if eps_tvd is None else eps_tvd, logits=self.logits,
+                    row_thr=self.row_thr, row_lse=self.row_lse, max_depth=self.max_depth, mode=mode,
+                    accept_len=self.accept_len, path_nodes=self.path_nodes, emitted=self.emitted,
+                    terminal=self.terminal, tvd_used=self.tvd_used)
+
+    def step(self, mode=WALK_SEQUENTIAL, w=None):
+        """One whole verification step: the four calls in order on the context's stream."""
+        self.attn()
+        self.lmhead(w)
+        self.accept()
+        self.select(mode)

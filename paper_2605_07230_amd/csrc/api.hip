@@ -1,0 +1,229 @@
+// C ABI of the tree-verification library: context, argument validation, dispatch.
+// Validation uses host-visible values only and happens before anything is enqueued.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+namespace {
+
+thread_local char g_hip_msg[256] = "no HIP error recorded";
+
+int hip_fail(hipError_t e) {
+  snprintf(g_hip_msg, sizeof(g_hip_msg), "HIP error %d: %s", (int)e, hipGetErrorString(e));
+  return CASCADE_EHIP;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool bad_float(float x) { return isnan(x); }
+
+}  // namespace
+
+extern "C" {
+
+const char* cascade_strerror(int status) {
+  switch (status) {
+    case CASCADE_OK: return "ok";
+    case CASCADE_EINVAL: return "invalid argument (null pointer, negative size, NaN, bad enum)";
+    case CASCADE_ESHAPE: return "shape exceeds the context limits or breaks a divisibility rule";
+    case CASCADE_EDTYPE: return "dtype not supported by this call";
+    case CASCADE_ENOMEM: return "workspace allocation failed";
+    case CASCADE_EHIP: return g_hip_msg;
+    case CASCADE_ETREE: return "a device-side precondition on the tree arrays was violated";
+    default: return "unknown status";
+  }
+}
+
+int cascade_create(cascade_ctx** out, const cascade_limits* lim, void* hip_stream) {
+  if (!out) return CASCADE_EINVAL;
+  *out = nullptr;
+  if (!lim) return CASCADE_EINVAL;
+  if (lim->max_rows <= 0 || lim->max_nodes_total <= 0 || lim->max_nodes_per_tree <= 0 || lim->max_prefix < 0 ||
+      lim->n_heads <= 0 || lim->head_dim <= 0 || lim->hidden <= 0 || lim->vocab <= 0)
+    return CASCADE_EINVAL;
+  if (lim->max_nodes_per_tree > CASCADE_MAX_TREE || lim->vocab > CASCADE_MAX_VOCAB || lim->head_dim > 256 ||
+      lim->max_nodes_per_tree > lim->max_nodes_total)
+    return CASCADE_ESHAPE;
+  cascade_ctx* c = new (std::nothrow) cascade_ctx;
+  if (!c) return CASCADE_ENOMEM;
+  memset(c, 0, sizeof(*c));
+  c->stream = (hipStream_t)hip_stream;
+  c->lim = *lim;
+  hipError_t e = hipGetDevice(&c->device);
+  if (e != hipSuccess) { delete c; return hip_fail(e); }
+  // split-KV partials: up to 16 splits, capped at 256 MiB (fewer splits are used if it does not fit)
+  const size_t per_split = (size_t)lim->max_nodes_total * lim->n_heads * (lim->head_dim + 2) * sizeof(float);
+  size_t attn = per_split * 16;
+  const size_t cap = (size_t)256 << 20;
+  if (attn > cap) attn = cap;
+  c->attn_ws_bytes = align_up(attn, 256);
+  c->ws_bytes = 256 + c->attn_ws_bytes;
+  e = hipMalloc((void**)&c->ws, c->ws_bytes);
+  if (e != hipSuccess) { delete c; (void)hipGetLastError(); return CASCADE_ENOMEM; }
+  c->dev_status = (int*)c->ws;
+  c->attn_ws = c->ws + 256;
+  e = hipMemsetAsync(c->ws, 0, 256, c->stream);
+  if (e != hipSuccess) { (void)hipFree(c->ws); delete c; return hip_fail(e); }
+  *out = c;
+  return CASCADE_OK;
+}
+
+int cascade_set_kernel_timing(cascade_ctx* ctx, int enable) {
+  if (!ctx) return CASCADE_EINVAL;
+  if (enable && !ctx->ev) {
+    const int n = CASCADE_K_COUNT * TIMING_RING * 2;
+    ctx->ev = new (std::nothrow) hipEvent_t[n];
+    if (!ctx->ev) return CASCADE_ENOMEM;
+    for (int i = 0; i < n; ++i) {
+      hipError_t e = hipEventCreate(&ctx->ev[i]);
+      if (e != hipSuccess) {
+        for (int j = 0; j < i; ++j) (void)hipEventDestroy(ctx->ev[j]);
+        delete[] ctx->ev;
+        ctx->ev = nullptr;
+        return hip_fail(e);
+      }
+    }
+  }
+  ctx->timing = enable != 0;
+  for (int k = 0; k < CASCADE_K_COUNT; ++k) ctx->ev_used[k] = 0;
+  return CASCADE_OK;
+}
+
+int cascade_read_kernel_timing(cascade_ctx* ctx, int kernel_id, double* total_ms, int32_t* launches) {
+  if (!ctx || !total_ms || !launches || kernel_id < 0 || kernel_id >= CASCADE_K_COUNT) return CASCADE_EINVAL;
+  *total_ms = 0.0;
+  *launches = 0;
+  if (!ctx->ev) return CASCADE_OK;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(e);
+  double sum = 0.0;
+  const int n = ctx->ev_used[kernel_id];
+  for (int i = 0; i < n; ++i) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, ctx->ev[(kernel_id * TIMING_RING + i) * 2], ctx->ev[(kernel_id * TIMING_RING + i) * 2 + 1]);
+    if (e != hipSuccess) return hip_fail(e);
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = n;
+  ctx->ev_used[kernel_id] = 0;
+  return CASCADE_OK;
+}
+
+int cascade_destroy(cascade_ctx* ctx) {
+  if (!ctx) return CASCADE_EINVAL;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (ctx->ev) {
+    for (int i = 0; i < CASCADE_K_COUNT * TIMING_RING * 2; ++i) (void)hipEventDestroy(ctx->ev[i]);
+    delete[] ctx->ev;
+  }
+  hipError_t e2 = hipFree(ctx->ws);
+  delete ctx;
+  if (e != hipSuccess) return hip_fail(e);
+  if (e2 != hipSuccess) return hip_fail(e2);
+  return CASCADE_OK;
+}
+
+int64_t cascade_workspace_bytes(const cascade_ctx* ctx) { return ctx ? (int64_t)ctx->ws_bytes : 0; }
+
+int cascade_device_status(cascade_ctx* ctx) {
+  if (!ctx) return CASCADE_EINVAL;
+  int flag = 0;
+  hipError_t e = hipMemcpyAsync(&flag, ctx->dev_status, sizeof(int), hipMemcpyDeviceToHost, ctx->stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(e);
+  if (flag) {
+    // cleared by a tiny kernel-free copy of a host zero (no memset node, so the call stays capturable-free)
+    static const int zero = 0;
+    e = hipMemcpyAsync(ctx->dev_status, &zero, sizeof(int), hipMemcpyHostToDevice, ctx->stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return CASCADE_ETREE;
+  }
+  return CASCADE_OK;
+}
+
+int tree_verify_attn(cascade_ctx* ctx, const tree_attn_args* a) {
+  if (!ctx || !a) return CASCADE_EINVAL;
+  if (!a->node_off || !a->parent || !a->prefix_len || !a->q || !a->k_tree || !a->v_tree || !a->out) return CASCADE_EINVAL;
+  if (a->n_rows < 0 || a->n_nodes_total < 0 || a->max_nodes_per_tree < 0 || a->max_prefix_len < 0) return CASCADE_EINVAL;
+  if (a->max_prefix_len > 0 && (!a->k_cache || !a->v_cache)) return CASCADE_EINVAL;
+  if (a->dtype != CASCADE_F32 && a->dtype != CASCADE_BF16) return CASCADE_EDTYPE;
+  if (a->n_heads <= 0 || a->n_kv_heads <= 0 || a->head_dim <= 0 || bad_float(a->scale) || a->scale < 0.f) return CASCADE_EINVAL;
+  if (a->n_heads % a->n_kv_heads != 0) return CASCADE_ESHAPE;
+  const cascade_limits& L = ctx->lim;
+  if (a->n_rows > L.max_rows || a->n_nodes_total > L.max_nodes_total || a->max_nodes_per_tree > L.max_nodes_per_tree ||
+      a->max_prefix_len > L.max_prefix || a->n_heads > L.n_heads || a->head_dim > L.head_dim)
+    return CASCADE_ESHAPE;
+  if (a->dtype == CASCADE_BF16) {
+    if (a->head_dim != 64 && a->head_dim != 128) return CASCADE_ESHAPE;
+    if ((a->cache_stride_row % 8) || (a->cache_stride_head % 8) || (a->cache_stride_pos % 8)) return CASCADE_ESHAPE;
+  } else {
+    if (a->head_dim > 256) return CASCADE_ESHAPE;
+  }
+  if (a->cache_stride_pos < a->head_dim && a->max_prefix_len > 1) return CASCADE_ESHAPE;
+  if (a->n_rows == 0 || a->n_nodes_total == 0) return CASCADE_OK;
+  hipError_t e = (a->dtype == CASCADE_BF16) ? launch_tree_attn_bf16(ctx, a) : launch_tree_attn_f32(ctx, a);
+  return e == hipSuccess ? CASCADE_OK : hip_fail(e);
+}
+
+int lmhead_softmax_cfg(cascade_ctx* ctx, const lmhead_args* a) {
+  if (!ctx || !a) return CASCADE_EINVAL;
+  if (!a->h_cond || !a->w || !a->logits || !a->row_max || !a->row_thr || !a->row_lse) return CASCADE_EINVAL;
+  if (a->dtype != CASCADE_F32 && a->dtype != CASCADE_BF16) return CASCADE_EDTYPE;
+  if (a->n_nodes < 0 || a->hidden <= 0 || a->vocab <= 0) return CASCADE_EINVAL;
+  if (bad_float(a->cfg_scale) || bad_float(a->temperature) || !(a->temperature > 0.f)) return CASCADE_EINVAL;
+  const cascade_limits& L = ctx->lim;
+  if (a->n_nodes > L.max_nodes_total || a->hidden > L.hidden || a->vocab > L.vocab || a->vocab > CASCADE_MAX_VOCAB)
+    return CASCADE_ESHAPE;
+  if (a->dtype == CASCADE_BF16) {
+    if ((a->hidden % 128) || (a->vocab % 64)) return CASCADE_ESHAPE;
+  } else {
+    if (a->hidden > 8192) return CASCADE_ESHAPE;
+  }
+  if (a->n_nodes == 0) return CASCADE_OK;
+  hipError_t e = (a->dtype == CASCADE_BF16) ? launch_lmhead_bf16(ctx, a) : launch_lmhead_f32(ctx, a);
+  if (e != hipSuccess) return hip_fail(e);
+  e = launch_row_stats(ctx, a);
+  return e == hipSuccess ? CASCADE_OK : hip_fail(e);
+}
+
+int cascade_accept(cascade_ctx* ctx, const accept_args* a) {
+  if (!ctx || !a) return CASCADE_EINVAL;
+  if (!a->node_off || !a->parent || !a->token || !a->h_cond || !a->logits || !a->row_thr || !a->row_lse || !a->q_tok ||
+      !a->m_int || !a->m_conv || !a->cos_parent || !a->n_int || !a->n_conv)
+    return CASCADE_EINVAL;
+  if (a->h_dtype != CASCADE_F32 && a->h_dtype != CASCADE_BF16) return CASCADE_EDTYPE;
+  if (a->n_prompts < 0 || a->n_nodes_total < 0 || a->hidden <= 0 || a->vocab <= 0) return CASCADE_EINVAL;
+  if (bad_float(a->tau_pos) || bad_float(a->tau_seq)) return CASCADE_EINVAL;
+  const cascade_limits& L = ctx->lim;
+  if (a->n_nodes_total > L.max_nodes_total || a->hidden > L.hidden || a->vocab > L.vocab) return CASCADE_ESHAPE;
+  if (a->h_dtype == CASCADE_BF16 && (a->hidden % 8)) return CASCADE_ESHAPE;
+  if (a->n_prompts == 0 || a->n_nodes_total == 0) return CASCADE_OK;
+  hipError_t e = launch_accept(ctx, a);
+  return e == hipSuccess ? CASCADE_OK : hip_fail(e);
+}
+
+int select_path(cascade_ctx* ctx, const select_args* a) {
+  if (!ctx || !a) return CASCADE_EINVAL;
+  if (!a->node_off || !a->parent || !a->token || !a->q_tok || !a->m_int || !a->m_conv || !a->n_int || !a->n_conv || !a->u ||
+      !a->u_bonus || !a->logits || !a->row_thr || !a->row_lse || !a->accept_len || !a->emitted || !a->terminal || !a->tvd_used)
+    return CASCADE_EINVAL;
+  if (a->n_prompts < 0 || a->n_nodes_total < 0 || a->vocab <= 0 || a->max_depth < 0) return CASCADE_EINVAL;
+  if (a->max_depth > 0 && !a->path_nodes) return CASCADE_EINVAL;
+  if (a->mode != CASCADE_WALK_SEQUENTIAL && a->mode != CASCADE_WALK_LONGEST) return CASCADE_EINVAL;
+  if (bad_float(a->eps_tvd) || a->eps_tvd < 0.f) return CASCADE_EINVAL;
+  const cascade_limits& L = ctx->lim;
+  if (a->n_nodes_total > L.max_nodes_total || a->vocab > L.vocab || a->max_depth > CASCADE_MAX_DEPTH) return CASCADE_ESHAPE;
+  if (a->n_prompts == 0) return CASCADE_OK;
+  hipError_t e = launch_select(ctx, a);
+  return e == hipSuccess ? CASCADE_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,493 @@
+// tree_verify_attn kernels for gfx950.
+//
+// Every node of a row attends the row's prefix KV positions plus its ancestors in the drafted
+// tree plus itself (Preliminaries: parallel target pass; tree decoding with a tree mask).
+//
+// bf16 path: one workgroup = (row, kv head, query super-block, kv split).  K tiles (64 keys) are
+// staged row-major in LDS, V tiles transposed ([d][key]) so that both MFMA operands are read as
+// contiguous 8/16-byte LDS words.  Scores are produced TRANSPOSED, S^T = K Q^T, with
+// v_mfma_f32_16x16x32_bf16: a lane then owns one query column, so the online-softmax statistics
+// are per-lane scalars and the probabilities are already laid out as the B operand of
+// O^T = V^T P^T.  The ancestor mask of the 64 tree keys of a tile is one 64-bit word per query,
+// built in LDS by climbing parent pointers.  Split-KV partials go through the workspace and a
+// small merge kernel; with one split the kernel writes the final output.
+//
+// f32 path: a plain one-workgroup-per-(node, head) kernel, used by the small fp32 configuration.
+#include "common.h"
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+struct AttnParams {
+  const int32_t* node_off;
+  const int32_t* parent;
+  const int32_t* prefix_len;
+  const void* q;
+  const void* k_tree;
+  const void* v_tree;
+  const void* k_cache;
+  const void* v_cache;
+  int64_t sr, sh, sp;
+  void* out;
+  float* lse;
+  float* ws_o;     // [n_split][N*Hq][D]
+  float* ws_ml;    // [n_split][N*Hq][2]
+  int* dev_status;
+  int n_heads, n_kv_heads, group;
+  int n_split, n_sb;
+  int n_rows_total;  // N * Hq
+  float scale_log2e;
+};
+
+// ------------------------------------------------------------------------------------------ f32
+// grid (N, Hq); 256 threads.  Keys are visited in chunks of 256 with a running max / sum.
+template <int DMAX>
+__global__ __launch_bounds__(256) void attn_f32_kernel(AttnParams p, int n_rows, int D) {
+  __shared__ float qs[DMAX];
+  __shared__ float sc[256];
+  __shared__ int anc[CASCADE_MAX_DEPTH + 2];
+  __shared__ float red[8];
+  __shared__ int s_row, s_nanc;
+  const int node = blockIdx.x, head = blockIdx.y, tid = threadIdx.x;
+  const int kvh = head / p.group;
+  if (tid == 0) {
+    int s = 0;
+    while (s + 1 < n_rows && p.node_off[s + 1] <= node) ++s;
+    s_row = s;
+    int lo = p.node_off[s];
+    int i = node - lo, n = 0;
+    while (i >= 0 && n < CASCADE_MAX_DEPTH + 1) {
+      anc[n++] = i;
+      int pi = p.parent[lo + i];
+      if (pi >= i) { atomicOr(p.dev_status, CASCADE_FLAG_PARENT); break; }
+      i = pi;
+    }
+    if (i >= 0 && n == CASCADE_MAX_DEPTH + 1) atomicOr(p.dev_status, CASCADE_FLAG_DEPTH);
+    s_nanc = n;
+  }
+  const float* q = (const float*)p.q + ((int64_t)node * p.n_heads + head) * D;
+  for (int d = tid; d < D; d += 256) qs[d] = q[d];
+  __syncthreads();
+  const int s = s_row, lo = p.node_off[s], P = p.prefix_len[s], nanc = s_nanc;
+  const int L = P + nanc;
+  const float* kc = (const float*)p.k_cache + s * p.sr + kvh * p.sh;
+  const float* vc = (const float*)p.v_cache + s * p.sr + kvh * p.sh;
+  const float* kt = (const float*)p.k_tree;
+  const float* vt = (const float*)p.v_tree;
+  float m = -INFINITY, l = 0.f, acc = 0.f;  // acc: output element tid (tid < D)
+  for (int base = 0; base < L; base += 256) {
+    const int j = base + tid;
+    float z = -INFINITY;
+    if (j < L) {
+      const float* kp = (j < P) ? kc + (int64_t)j * p.sp
+                                : kt + ((int64_t)(lo + anc[j - P]) * p.n_kv_heads + kvh) * D;
+      float dot = 0.f;
+      for (int d = 0; d < D; ++d) dot = fmaf(qs[d], kp[d], dot);
+      z = dot * p.scale_log2e;
+    }
+    float cm = wave_max(z);
+    if ((tid & 63) == 0) red[tid >> 6] = cm;
+    __syncthreads();
+    cm = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float m_new = fmaxf(m, cm);
+    const float alpha = exp2f(m - m_new);   // m = -inf on the first chunk gives 0
+    const float e = (j < L) ? exp2f(z - m_new) : 0.f;
+    sc[tid] = e;
+    float cs = wave_sum(e);
+    if ((tid & 63) == 0) red[4 + (tid >> 6)] = cs;
+    __syncthreads();
+    l = l * alpha + (red[4] + red[5] + red[6] + red[7]);
+    m = m_new;
+    if (tid < D) {
+      acc *= alpha;
+      const int cnt = min(256, L - base);
+      for (int jj = 0; jj < cnt; ++jj) {
+        const int j2 = base + jj;
+        const float* vp = (j2 < P) ? vc + (int64_t)j2 * p.sp
+                                   : vt + ((int64_t)(lo + anc[j2 - P]) * p.n_kv_heads + kvh) * D;
+        acc = fmaf(sc[jj], vp[tid], acc);
+      }
+    }
+    __syncthreads();
+  }
+  if (tid < D) ((float*)p.out)[((int64_t)node * p.n_heads + head) * D + tid] = acc / l;
+  if (tid == 0 && p.lse) p.lse[(int64_t)node * p.n_heads + head] = m * LN2 + logf(l);
+}
+
+// ----------------------------------------------------------------------------------------- bf16
+constexpr int KT = 64;  // keys per tile
+
+template <int D>
+struct AttnSmem {
+  static constexpr int KP = D + 8;     // K row pitch (elements)
+  static constexpr int VP = KT + 4;    // V^T row pitch (elements): 136 B, conflict-free 8-byte reads
+  uint16_t k[KT * KP];
+  uint16_t vt[D * VP];
+  int parent[CASCADE_MAX_TREE];
+  unsigned long long anc[256];
+};
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  return (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
+}
+
+union Frag8 {
+  bf16x8 v;
+  uint4 u;
+  uint2 h[2];
+};
+
+// NQ = 16-row query blocks per wave (the workgroup covers 64*NQ query rows).
+template <int D, int NQ, bool SPLIT>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
+  using SM = AttnSmem<D>;
+  __shared__ SM sm;
+  constexpr int KS = D / 32;   // 32-wide d steps of the score MFMA
+  constexpr int DB = D / 16;   // 16-wide d blocks of the output
+  constexpr int DC = D / 8;    // 16-byte chunks per row
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int s = blockIdx.z, kvh = blockIdx.y;
+  const int split = blockIdx.x % p.n_split, sb = blockIdx.x / p.n_split;
+  const int lo = p.node_off[s];
+  const int T = p.node_off[s + 1] - lo;
+  const int P = p.prefix_len[s];
+  const int G = p.group;
+  const int M = T * G;
+  const int row0 = sb * 64 * NQ;
+  if (row0 >= M || T > CASCADE_MAX_TREE) return;
+  const int n_pt = (P + KT - 1) / KT, n_tt = (T + KT - 1) / KT, nt = n_pt + n_tt;
+  const int per = (nt + p.n_split - 1) / p.n_split;
+  const int t_begin = split * per, t_end = min(nt, t_begin + per);
+
+  const uint16_t* kc = (const uint16_t*)p.k_cache + s * p.sr + kvh * p.sh;
+  const uint16_t* vc = (const uint16_t*)p.v_cache + s * p.sr + kvh * p.sh;
+  const uint16_t* ktr = (const uint16_t*)p.k_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D;
+  const uint16_t* vtr = (const uint16_t*)p.v_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D;
+  const int64_t tree_pitch = (int64_t)p.n_kv_heads * D;
+
+  if (t_end > n_pt) {
+    for (int i = tid; i < T; i += 256) {
+      int pi = p.parent[lo + i];
+      if (pi >= i || pi < -1 || (i == 0 && pi != -1) || (i > 0 && pi < 0)) {
+        atomicOr(p.dev_status, CASCADE_FLAG_PARENT);
+        pi = (i == 0) ? -1 : 0;   // keep the climb finite
+      }
+      sm.parent[i] = pi;
+    }
+  }
+
+  // query fragments (B operand of S^T): lane = (query l16, d group g)
+  Frag8 qf[NQ][KS];
+  int64_t out_row[NQ];   // index into [N*Hq] or -1
+  int q_node[NQ];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    const int r = row0 + 16 * (wave + 4 * n) + l16;
+    const bool ok = r < M;
+    const int i = ok ? r % T : 0, hg = ok ? r / T : 0;
+    q_node[n] = ok ? i : -1;
+    const int64_t rowg = (int64_t)(lo + i) * p.n_heads + kvh * G + hg;
+    out_row[n] = ok ? rowg : -1;
+    const uint16_t* qp = (const uint16_t*)p.q + rowg * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ok) qf[n][ks].u = *(const uint4*)(qp + 32 * ks);
+      else qf[n][ks].u = make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  f32x4 ot[NQ][DB];
+  float m_run[NQ], l_run[NQ];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    m_run[n] = -INFINITY;
+    l_run[n] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) ot[n][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int t = t_begin; t < t_end; ++t) {
+    const bool tree_tile = t >= n_pt;
+    const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
+    const int klimit = tree_tile ? T : P;
+    const uint16_t* ksrc = tree_tile ? ktr : kc;
+    const uint16_t* vsrc = tree_tile ? vtr : vc;
+    const int64_t pitch = tree_tile ? tree_pitch : p.sp;
+    __syncthreads();   // previous tile fully consumed
+    // K tile, row-major
+#pragma unroll
+    for (int it = 0; it < (KT * DC) / 256; ++it) {
+      const int c = tid + 256 * it;
+      const int key = c / DC, dc = c % DC;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (kbase + key < klimit) v = *(const uint4*)(ksrc + (int64_t)(kbase + key) * pitch + 8 * dc);
+      *(uint4*)(&sm.k[key * SM::KP + 8 * dc]) = v;
+    }
+    // V tile, transposed: a thread takes 4 keys x 8 d and writes 8 rows of 4 keys
+    if (tid < 16 * DC) {
+      const int dc = tid % DC, kg = tid / DC;
+      uint32_t w[4][4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int key = kbase + 4 * kg + r;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (key < klimit) v = *(const uint4*)(vsrc + (int64_t)key * pitch + 8 * dc);
+        w[r][0] = v.x; w[r][1] = v.y; w[r][2] = v.z; w[r][3] = v.w;
+      }
+#pragma unroll
+      for (int dd = 0; dd < 8; ++dd) {
+        const int wi = dd >> 1;
+        uint2 o;
+        if (dd & 1) {
+          o.x = (w[0][wi] >> 16) | (w[1][wi] & 0xffff0000u);
+          o.y = (w[2][wi] >> 16) | (w[3][wi] & 0xffff0000u);
+        } else {
+          o.x = (w[0][wi] & 0xffffu) | (w[1][wi] << 16);
+          o.y = (w[2][wi] & 0xffffu) | (w[3][wi] << 16);
+        }
+        *(uint2*)(&sm.vt[(8 * dc + dd) * SM::VP + 4 * kg]) = o;
+      }
+    }
+    if (tree_tile) {
+      // ancestor-or-self bits of the tile's 64 tree keys, one word per query row of the workgroup
+      if (tid < 64 * NQ) {
+        const int r = row0 + tid;
+        unsigned long long wbits = 0ull;
+        if (r < M) {
+          int a = r % T;
+          int guard = 0;
+          while (a >= 0 && guard++ <= CASCADE_MAX_TREE) {
+            const int rel = a - kbase;
+            if (rel < 0) break;   // ancestors only get smaller
+            if (rel < 64) wbits |= 1ull << rel;
+            a = sm.parent[a];
+          }
+        }
+        sm.anc[tid] = wbits;
+      }
+    }
+    __syncthreads();
+
+    // S^T = K Q^T : st[n][kt] holds keys 16*kt + 4*g + c for query l16
+    f32x4 st[NQ][4];
+#pragma unroll
+    for (int n = 0; n < NQ; ++n)
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) st[n][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        Frag8 kf;
+        kf.u = *(const uint4*)(&sm.k[(16 * kt + l16) * SM::KP + 32 * ks + 8 * g]);
+#pragma unroll
+        for (int n = 0; n < NQ; ++n)
+          st[n][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[n][ks].v, st[n][kt], 0, 0, 0);
+      }
+    }
+
+    // mask + online softmax; probabilities packed as the B operand of the second MFMA
+    Frag8 pf[NQ][2];
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      unsigned long long valid;
+      if (tree_tile) {
+        valid = sm.anc[16 * (wave + 4 * n) + l16];
+      } else {
+        const int rem = klimit - kbase;
+        valid = rem >= 64 ? ~0ull : ((1ull << rem) - 1ull);
+      }
+      if (q_node[n] < 0) valid = 0ull;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int kk = 16 * kt + 4 * g + c;
+          float z = st[n][kt][c] * p.scale_log2e;
+          z = ((valid >> kk) & 1ull) ? z : -INFINITY;
+          st[n][kt][c] = z;
+          mx = fmaxf(mx, z);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      const float m_new = fmaxf(m_run[n], mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = exp2f(m_run[n] - m_use);   // -inf - finite = -inf -> 0
+      float ls = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float e = exp2f(st[n][kt][c] - m_use);
+          st[n][kt][c] = e;
+          ls += e;
+        }
+      l_run[n] = l_run[n] * alpha + ls;
+      m_run[n] = m_new;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) ot[n][db] *= alpha;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        pf[n][j].u.x = pack_bf16x2(st[n][2 * j][0], st[n][2 * j][1]);
+        pf[n][j].u.y = pack_bf16x2(st[n][2 * j][2], st[n][2 * j][3]);
+        pf[n][j].u.z = pack_bf16x2(st[n][2 * j + 1][0], st[n][2 * j + 1][1]);
+        pf[n][j].u.w = pack_bf16x2(st[n][2 * j + 1][2], st[n][2 * j + 1][3]);
+      }
+    }
+
+    // O^T += V^T P^T : A operand rows = d, k slots = keys {32j+4g+0..3, 32j+16+4g+0..3}
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        Frag8 vf;
+        const uint16_t* vp = &sm.vt[(16 * db + l16) * SM::VP + 32 * j + 4 * g];
+        vf.h[0] = *(const uint2*)(vp);
+        vf.h[1] = *(const uint2*)(vp + 16);
+#pragma unroll
+        for (int n = 0; n < NQ; ++n)
+          ot[n][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[n][j].v, ot[n][db], 0, 0, 0);
+      }
+    }
+  }
+
+  // epilogue: lane (query l16, g) owns d = 16*db + 4*g + c
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    float l = l_run[n];
+    l += __shfl_xor(l, 16, WAVE);
+    l += __shfl_xor(l, 32, WAVE);
+    if (out_row[n] < 0) continue;
+    if (SPLIT) {
+      float* wo = p.ws_o + ((int64_t)split * p.n_rows_total + out_row[n]) * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) *(f32x4*)(wo + 16 * db + 4 * g) = ot[n][db];
+      if (g == 0) {
+        float* wm = p.ws_ml + ((int64_t)split * p.n_rows_total + out_row[n]) * 2;
+        wm[0] = m_run[n];
+        wm[1] = l;
+      }
+    } else {
+      const float inv = 1.f / l;
+      uint16_t* o = (uint16_t*)p.out + out_row[n] * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        uint2 w;
+        w.x = pack_bf16x2(ot[n][db][0] * inv, ot[n][db][1] * inv);
+        w.y = pack_bf16x2(ot[n][db][2] * inv, ot[n][db][3] * inv);
+        *(uint2*)(o + 16 * db + 4 * g) = w;
+      }
+      if (g == 0 && p.lse) p.lse[out_row[n]] = m_run[n] * LN2 + logf(l);
+    }
+  }
+}
+
+// one block of D threads per output row: log-sum-exp merge of the split partials
+template <int D>
+__global__ __launch_bounds__(D) void attn_merge_kernel(AttnParams p) {
+  const int64_t row = blockIdx.x;
+  const int d = threadIdx.x;
+  float m = -INFINITY;
+  for (int c = 0; c < p.n_split; ++c) m = fmaxf(m, p.ws_ml[((int64_t)c * p.n_rows_total + row) * 2]);
+  float o = 0.f, l = 0.f;
+  for (int c = 0; c < p.n_split; ++c) {
+    const float* ml = p.ws_ml + ((int64_t)c * p.n_rows_total + row) * 2;
+    const float mc = ml[0];
+    if (mc == -INFINITY) continue;
+    const float w = exp2f(mc - m);
+    l += w * ml[1];
+    o += w * p.ws_o[((int64_t)c * p.n_rows_total + row) * D + d];
+  }
+  ((uint16_t*)p.out)[row * D + d] = f32_to_bf16_bits(o / l);
+  if (d == 0 && p.lse) p.lse[row] = m * LN2 + logf(l);
+}
+
+AttnParams make_params(cascade_ctx* ctx, const tree_attn_args* a) {
+  AttnParams p;
+  p.node_off = a->node_off;
+  p.parent = a->parent;
+  p.prefix_len = a->prefix_len;
+  p.q = a->q;
+  p.k_tree = a->k_tree;
+  p.v_tree = a->v_tree;
+  p.k_cache = a->k_cache;
+  p.v_cache = a->v_cache;
+  p.sr = a->cache_stride_row;
+  p.sh = a->cache_stride_head;
+  p.sp = a->cache_stride_pos;
+  p.out = a->out;
+  p.lse = a->lse;
+  p.ws_o = nullptr;
+  p.ws_ml = nullptr;
+  p.dev_status = ctx->dev_status;
+  p.n_heads = a->n_heads;
+  p.n_kv_heads = a->n_kv_heads;
+  p.group = a->n_heads / a->n_kv_heads;
+  p.n_split = 1;
+  p.n_sb = 1;
+  p.n_rows_total = a->n_nodes_total * a->n_heads;
+  const float scale = a->scale != 0.f ? a->scale : 1.f / sqrtf((float)a->head_dim);
+  p.scale_log2e = scale * LOG2E;
+  return p;
+}
+
+template <int D, int NQ>
+hipError_t launch_bf16_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
+  hipStream_t st = ctx->stream;
+  if (p.n_split > 1) {
+    {
+      KernelTimer t(ctx, CASCADE_K_ATTN);
+      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, true>), grid, dim3(256), 0, st, p);
+    }
+    KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
+    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(p.n_rows_total), dim3(D), 0, st, p);
+  } else {
+    KernelTimer t(ctx, CASCADE_K_ATTN);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, false>), grid, dim3(256), 0, st, p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_tree_attn_f32(cascade_ctx* ctx, const tree_attn_args* a) {
+  AttnParams p = make_params(ctx, a);
+  dim3 grid(a->n_nodes_total, a->n_heads);
+  KernelTimer t(ctx, CASCADE_K_ATTN);
+  hipLaunchKernelGGL((attn_f32_kernel<256>), grid, dim3(256), 0, ctx->stream, p, a->n_rows, a->head_dim);
+  return hipGetLastError();
+}
+
+hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a) {
+  AttnParams p = make_params(ctx, a);
+  const int M = a->max_nodes_per_tree * p.group;   // query rows per (row, kv head)
+  const int NQ = M <= 64 ? 1 : (M <= 128 ? 2 : 4);
+  p.n_sb = (M + 64 * NQ - 1) / (64 * NQ);
+  const int n_tiles = (a->max_prefix_len + KT - 1) / KT + (a->max_nodes_per_tree + KT - 1) / KT;
+  const long base_wgs = (long)a->n_rows * a->n_kv_heads * p.n_sb;
+  int n_split = (int)((512 + base_wgs - 1) / base_wgs);
+  if (n_split > n_tiles) n_split = n_tiles;
+  if (n_split > 16) n_split = 16;
+  const size_t per_split = (size_t)p.n_rows_total * (a->head_dim + 2) * sizeof(float);
+  if (n_split > 1 && per_split * n_split > ctx->attn_ws_bytes) n_split = (int)(ctx->attn_ws_bytes / per_split);
+  if (n_split < 1) n_split = 1;
+  p.n_split = n_split;
+  if (n_split > 1) {
+    p.ws_o = (float*)ctx->attn_ws;
+    p.ws_ml = (float*)(ctx->attn_ws + (size_t)n_split * p.n_rows_total * a->head_dim * sizeof(float));
+  }
+  dim3 grid(n_split * p.n_sb, a->n_kv_heads, a->n_rows);
+  if (a->head_dim == 128) {
+    if (NQ == 1) return launch_bf16_t<128, 1>(ctx, p, grid);
+    if (NQ == 2) return launch_bf16_t<128, 2>(ctx, p, grid);
+    return launch_bf16_t<128, 4>(ctx, p, grid);
+  } else {
+    if (NQ == 1) return launch_bf16_t<64, 1>(ctx, p, grid);
+    if (NQ == 2) return launch_bf16_t<64, 2>(ctx, p, grid);
+    return launch_bf16_t<64, 4>(ctx, p, grid);
+  }
+}

@@ -1,0 +1,101 @@
+// Shared declarations of the gfx950 tree-verification library (internal; the public ABI is
+// include/cascade_verify.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/cascade_verify.h"
+
+// ----------------------------------------------------------------------------------------------
+// context
+struct cascade_ctx {
+  hipStream_t stream;
+  cascade_limits lim;
+  int device;
+  char* ws;               // device workspace
+  size_t ws_bytes;
+  int* dev_status;        // one int at the start of ws: sticky precondition flag
+  char* attn_ws;          // split-KV partials
+  size_t attn_ws_bytes;
+  // optional per-kernel timing with HIP events on the ctx stream (cascade_set_kernel_timing)
+  bool timing;
+  hipEvent_t* ev;         // [CASCADE_K_COUNT][TIMING_RING][2], created on first enable
+  int ev_used[8];
+};
+
+enum { TIMING_RING = 2048 };
+
+// Brackets one kernel launch with two events when timing is on; otherwise does nothing.
+struct KernelTimer {
+  cascade_ctx* c;
+  int id, slot;
+  KernelTimer(cascade_ctx* ctx, int kernel_id) : c(ctx), id(kernel_id), slot(-1) {
+    if (c && c->timing && c->ev && c->ev_used[id] < TIMING_RING) {
+      slot = c->ev_used[id]++;
+      (void)hipEventRecord(c->ev[(id * TIMING_RING + slot) * 2], c->stream);
+    }
+  }
+  ~KernelTimer() {
+    if (slot >= 0) (void)hipEventRecord(c->ev[(id * TIMING_RING + slot) * 2 + 1], c->stream);
+  }
+};
+
+// flags OR-ed into *dev_status by kernels
+enum {
+  CASCADE_FLAG_PARENT = 1,   // parent[i] >= i or < -1, or a second root
+  CASCADE_FLAG_WIDTH = 2,    // more than CASCADE_MAX_WIDTH children
+  CASCADE_FLAG_TOKEN = 4,    // token outside [0, vocab)
+  CASCADE_FLAG_DEPTH = 8     // path longer than max_depth
+};
+
+// launchers (one translation unit each); all return hipError_t of the launch
+hipError_t launch_tree_attn_f32(cascade_ctx* ctx, const tree_attn_args* a);
+hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a);
+hipError_t launch_lmhead_f32(cascade_ctx* ctx, const lmhead_args* a);
+hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a);
+hipError_t launch_row_stats(cascade_ctx* ctx, const lmhead_args* a);
+hipError_t launch_accept(cascade_ctx* ctx, const accept_args* a);
+hipError_t launch_select(cascade_ctx* ctx, const select_args* a);
+
+// ----------------------------------------------------------------------------------------------
+// device helpers
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define WAVE 64
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even float -> bf16 bits (NaN kept quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// element loads that widen to float, for kernels templated on the storage type
+template <typename T>
+__device__ __forceinline__ float load_f32(const T* p);
+template <>
+__device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_f32<uint16_t>(const uint16_t* p) { return bf16_bits_to_f32(*p); }

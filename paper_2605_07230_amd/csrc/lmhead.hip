@@ -1,0 +1,299 @@
+// lmhead_softmax_cfg kernels for gfx950: final projection with the guidance mix in the epilogue
+// (Sec. 4.2: the O(hV) projection dominates; App. "Configuration Details": guidance scale,
+// temperature, top-k), then one kernel for the per-row softmax statistics.
+//
+// bf16 projection: a workgroup owns 64 vocabulary columns x 64 nodes (conditional and
+// unconditional rows of the same nodes, so the mix happens in registers).  Its four waves split
+// the hidden dimension; every wave streams its own slices of W and H straight from global memory
+// into v_mfma_f32_32x32x16_bf16 operand registers (both operands are k-contiguous, so a lane's
+// 8 operand values are one 16-byte load) and the four partial tiles are summed through LDS once
+// at the end.  Nothing is shared between waves inside the main loop, so it has no barriers.
+#include "common.h"
+
+namespace {
+
+struct LmParams {
+  const void* h_cond;
+  const void* h_uncond;
+  const void* w;
+  float* logits;
+  float* row_max;
+  float* row_thr;
+  float* row_lse;
+  int n_nodes, hidden, vocab;
+  int n_mchunks;
+  float cfg_scale, temperature;
+  int top_k;
+};
+
+// ------------------------------------------------------------------------------------------ f32
+// grid (ceil(V/256), N); the two hidden-state rows sit in LDS, a thread owns one vocabulary entry.
+__global__ __launch_bounds__(256) void lmhead_f32_kernel(LmParams p) {
+  extern __shared__ float hs[];
+  const int node = blockIdx.y, v = blockIdx.x * 256 + threadIdx.x;
+  const int K = p.hidden;
+  const bool cfg = p.h_uncond != nullptr;
+  const float* hc = (const float*)p.h_cond + (int64_t)node * K;
+  const float* hu = cfg ? (const float*)p.h_uncond + (int64_t)node * K : nullptr;
+  for (int k = threadIdx.x; k < K; k += 256) {
+    hs[k] = hc[k];
+    if (cfg) hs[K + k] = hu[k];
+  }
+  __syncthreads();
+  if (v >= p.vocab) return;
+  const float* wr = (const float*)p.w + (int64_t)v * K;
+  float lc = 0.f, lu = 0.f;
+  for (int k = 0; k < K; ++k) {
+    const float wv = wr[k];
+    lc = fmaf(hs[k], wv, lc);
+    if (cfg) lu = fmaf(hs[K + k], wv, lu);
+  }
+  float gmix = cfg ? lu + p.cfg_scale * (lc - lu) : lc;
+  p.logits[(int64_t)node * p.vocab + v] = gmix / p.temperature;
+}
+
+// ----------------------------------------------------------------------------------------- bf16
+union Frag8 {
+  bf16x8 v;
+  uint4 u;
+};
+
+template <bool CFG>
+struct Group {   // operands of 4 consecutive k16 steps
+  static constexpr int NA = CFG ? 4 : 2;
+  Frag8 a[4][NA];
+  Frag8 b[4][2];
+};
+
+template <bool CFG>
+__global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmParams p) {
+  constexpr int NA = CFG ? 4 : 2;   // 32-row operand blocks: cond0, cond1, (uncond0, uncond1)
+  extern __shared__ float red[];    // [4 waves][NA*2 acc][16 regs][64 lanes]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r32 = lane & 31, half = lane >> 5;
+  const int K = p.hidden;
+
+  // XCD-aware order: the 8 XCDs take workgroups round-robin; give each XCD a contiguous range of
+  // logical ids so that the m-chunks sharing one W tile meet in the same L2.
+  int logical = blockIdx.x;
+  const int nwg = gridDim.x;
+  if ((nwg & 7) == 0) logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
+  const int ntile = logical / p.n_mchunks, mc = logical % p.n_mchunks;
+  const int v0 = ntile * 64, node0 = mc * 64;
+
+  const uint16_t* ap[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int node = min(node0 + 32 * (i & 1) + r32, p.n_nodes - 1);   // rows past the end are clamped, never stored
+    const uint16_t* base = (i < 2) ? (const uint16_t*)p.h_cond : (const uint16_t*)p.h_uncond;
+    ap[i] = base + (int64_t)node * K + 8 * half;
+  }
+  const uint16_t* bp[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) bp[j] = (const uint16_t*)p.w + (int64_t)(v0 + 32 * j + r32) * K + 8 * half;
+
+  f32x16 acc[NA][2];
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // this wave's k groups (64 wide): 128-wide slices wave, wave+4, ... of the hidden dimension
+  const int n_slices = (K / 128 - wave + 3) / 4;   // K is a multiple of 128
+  const int n_groups = 2 * n_slices;
+  auto k_of = [&](int gi) { return (wave + 4 * (gi >> 1)) * 128 + 64 * (gi & 1); };
+  auto load_group = [&](Group<CFG>& G, int k) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) G.a[s][i].u = *(const uint4*)(ap[i] + k + 16 * s);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) G.b[s][j].u = *(const uint4*)(bp[j] + k + 16 * s);
+    }
+  };
+  auto compute_group = [&](const Group<CFG>& G) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int i = 0; i < NA; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(G.a[s][i].v, G.b[s][j].v, acc[i][j], 0, 0, 0);
+  };
+
+  Group<CFG> g0, g1;
+  if (n_groups > 0) load_group(g0, k_of(0));
+  for (int gi = 0; gi < n_groups; gi += 2) {   // n_groups is even
+    load_group(g1, k_of(gi + 1));
+    compute_group(g0);
+    if (gi + 2 < n_groups) load_group(g0, k_of(gi + 2));
+    compute_group(g1);
+  }
+
+  // cross-wave reduction and epilogue
+  constexpr int NACC = NA * 2;
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[((wave * NACC + i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+  __syncthreads();
+  const int nbk = wave >> 1, nb = wave & 1;
+  const float inv_t = 1.f / p.temperature;
+  (void)inv_t;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float c = 0.f, u = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      c += red[((w * NACC + nbk * 2 + nb) * 16 + r) * 64 + lane];
+      if (CFG) u += red[((w * NACC + (2 + nbk) * 2 + nb) * 16 + r) * 64 + lane];
+    }
+    const float gmix = CFG ? u + p.cfg_scale * (c - u) : c;
+    const int node = node0 + 32 * nbk + 8 * (r >> 2) + 4 * half + (r & 3);
+    if (node < p.n_nodes) p.logits[(int64_t)node * p.vocab + v0 + 32 * nb + r32] = gmix / p.temperature;
+  }
+}
+
+// ------------------------------------------------------------------------------------ row stats
+// One workgroup of 1024 threads per row; the row lives in registers (VPT values per thread).
+// row_max, exact k-th largest (bitwise radix select on order-preserving integer keys), and
+// log-sum-exp over the kept entries.
+__device__ __forceinline__ uint32_t f32_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_f32(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+template <int VPT>
+__global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
+  __shared__ float fred[16];
+  __shared__ int ired[2][16];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int V = p.vocab;
+  const float* g = p.logits + (int64_t)row * V;
+  // the row is held as order-preserving integer keys; values are recovered from them when needed
+  uint32_t key[VPT];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int v = tid + 1024 * i;
+    const float xv = v < V ? g[v] : -INFINITY;
+    key[i] = f32_key(xv);
+    mx = fmaxf(mx, xv);
+  }
+  mx = wave_max(mx);
+  if (lane == 0) fred[wave] = mx;
+  __syncthreads();
+  mx = fred[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, fred[w]);
+
+  uint32_t thr_key = 0;            // key of -inf or below: keeps everything
+  float thr = -INFINITY;
+  if (p.top_k > 0 && p.top_k < V) {
+    uint32_t prefix = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = prefix | (1u << bit);
+      int cnt = 0;
+#pragma unroll
+      for (int i = 0; i < VPT; ++i) cnt += __popcll(__ballot(key[i] >= cand));
+      const int buf = bit & 1;
+      if (lane == 0) ired[buf][wave] = cnt;
+      __syncthreads();
+      int tot = 0;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) tot += ired[buf][w];
+      if (tot >= p.top_k) prefix = cand;
+    }
+    thr_key = prefix;
+    thr = key_f32(prefix);
+  }
+  float se = 0.f;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int v = tid + 1024 * i;
+    se += (v < V && key[i] >= thr_key) ? __expf(key_f32(key[i]) - mx) : 0.f;
+  }
+  se = wave_sum(se);
+  __syncthreads();
+  if (lane == 0) fred[wave] = se;
+  __syncthreads();
+  if (tid == 0) {
+    float tot = 0.f;
+    for (int w = 0; w < 16; ++w) tot += fred[w];
+    p.row_max[row] = mx;
+    p.row_thr[row] = thr;
+    p.row_lse[row] = mx + logf(tot);
+  }
+}
+
+LmParams make_params(const lmhead_args* a) {
+  LmParams p;
+  p.h_cond = a->h_cond;
+  p.h_uncond = a->h_uncond;
+  p.w = a->w;
+  p.logits = a->logits;
+  p.row_max = a->row_max;
+  p.row_thr = a->row_thr;
+  p.row_lse = a->row_lse;
+  p.n_nodes = a->n_nodes;
+  p.hidden = a->hidden;
+  p.vocab = a->vocab;
+  p.n_mchunks = (a->n_nodes + 63) / 64;
+  p.cfg_scale = a->cfg_scale;
+  p.temperature = a->temperature;
+  p.top_k = a->top_k;
+  return p;
+}
+
+}  // namespace
+
+hipError_t launch_lmhead_f32(cascade_ctx* ctx, const lmhead_args* a) {
+  hipStream_t stream = ctx->stream;
+  KernelTimer t(ctx, CASCADE_K_LMHEAD);
+  LmParams p = make_params(a);
+  dim3 grid((a->vocab + 255) / 256, a->n_nodes);
+  const size_t smem = (size_t)a->hidden * sizeof(float) * (a->h_uncond ? 2 : 1);
+  hipLaunchKernelGGL(lmhead_f32_kernel, grid, dim3(256), smem, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
+  hipStream_t stream = ctx->stream;
+  LmParams p = make_params(a);
+  const int grid = (a->vocab / 64) * p.n_mchunks;
+  hipError_t e;
+  if (a->h_uncond) {
+    const size_t smem = 4 * 8 * 16 * 64 * sizeof(float);
+    static bool attr_done = false;
+    if (!attr_done) {
+      e = hipFuncSetAttribute((const void*)lmhead_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (e != hipSuccess) return e;
+      attr_done = true;
+    }
+    KernelTimer t(ctx, CASCADE_K_LMHEAD);
+    hipLaunchKernelGGL(lmhead_bf16_kernel<true>, dim3(grid), dim3(256), smem, stream, p);
+  } else {
+    const size_t smem = 4 * 4 * 16 * 64 * sizeof(float);
+    KernelTimer t(ctx, CASCADE_K_LMHEAD);
+    hipLaunchKernelGGL(lmhead_bf16_kernel<false>, dim3(grid), dim3(256), smem, stream, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_row_stats(cascade_ctx* ctx, const lmhead_args* a) {
+  hipStream_t stream = ctx->stream;
+  KernelTimer t(ctx, CASCADE_K_ROW_STATS);
+  LmParams p = make_params(a);
+  const int V = a->vocab;
+  if (V <= 4096) hipLaunchKernelGGL(row_stats_kernel<4>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
+  else if (V <= 16384) hipLaunchKernelGGL(row_stats_kernel<16>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
+  else hipLaunchKernelGGL(row_stats_kernel<64>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
+  return hipGetLastError();
+}

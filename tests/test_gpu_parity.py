@@ -1,0 +1,183 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU checker on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_07230_amd import binding
+from paper_2605_07230_amd import workloads as wl
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_tiny_f32_whole_step(seed):
+    inp = wl.make_config(0, seed)
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds)
+    pu.check_lmhead(inp, ds)
+    pu.check_accept_and_path(inp, ds)
+
+
+@pytest.mark.parametrize("variant", ["topk", "harsh_drafter", "conv_dups", "longest", "strict", "zero_budget"])
+def test_tiny_f32_variants(variant):
+    kw = {}
+    if variant == "topk":
+        kw = dict(top_k=256)
+    inp = wl.make_config(0, 3, **kw)
+    mode = binding.WALK_SEQUENTIAL
+    if variant == "harsh_drafter":
+        inp.draft_prob = (inp.draft_prob * 3).astype(np.float32)           # q/p around 1/3: many rejections
+    if variant == "conv_dups":
+        rng = np.random.default_rng(5)
+        for a, c in [(1, 3), (2, 6), (5, 11)]:                               # child nearly equal to its parent
+            inp.h_cond[c] = inp.h_cond[a] + np.float32(0.1) * rng.standard_normal(inp.hidden).astype(np.float32)
+        inp.draft_prob = (inp.draft_prob * 2).astype(np.float32)
+    if variant == "longest":
+        inp.draft_prob = (inp.draft_prob * 2).astype(np.float32)
+        mode = binding.WALK_LONGEST
+    if variant == "strict":
+        inp.tau_pos = inp.tau_seq = 2.0
+    if variant == "zero_budget":
+        inp.eps_tvd = 0.0
+    ds = pu.run_gpu_step(inp, mode)
+    pu.check_lmhead(inp, ds)
+    acc, res = pu.check_accept_and_path(inp, ds, mode)
+    if variant in ("strict", "zero_budget"):
+        assert np.all(ds.tvd_used.cpu().numpy() == 0)
+    if variant == "conv_dups":
+        assert acc.n_conv.sum() >= 3
+
+
+@pytest.mark.parametrize("seed", [0, 3])
+def test_janus_shaped_bf16_whole_step(seed):
+    inp = wl.make_config(1, seed)
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds, heads=[0, 5, 31])
+    pu.check_lmhead(inp, ds)
+    pu.check_accept_and_path(inp, ds)
+    ds.select(binding.WALK_LONGEST)
+    pu.check_accept_and_path(inp, ds, binding.WALK_LONGEST)
+
+
+def test_janus_shaped_threshold_pairs():
+    inp = wl.make_config(1, 4)
+    ds = pu.run_gpu_step(inp)
+    for tp, ts in [(0.85, 0.5), (0.9, 0.9), (2.0, 2.0), (0.85, 2.0), (2.0, 0.5)]:
+        ds.accept(tp, ts)
+        ds.select()
+        pu.check_accept_and_path(inp, ds, tau_pos=tp, tau_seq=ts)
+
+
+def test_lumina_shaped_bf16_sampled():
+    inp = wl.make_config(2, 0)
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds, heads=[3, 17])
+    pu.check_lmhead(inp, ds, nodes=[0, 1, 7, 30, 59])
+    pu.check_accept_and_path(inp, ds)
+
+
+def test_batched_ragged_bf16():
+    inp = wl.make_config(3, 0)
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds, rows=[0, 1, 6, 15], heads=[0, 13])
+    nodes = np.unique(np.concatenate([inp.node_off[:-1], inp.node_off[1:] - 1, np.arange(0, inp.n_nodes, 37)]))
+    pu.check_lmhead(inp, ds, nodes=nodes)
+    pu.check_accept_and_path(inp, ds)
+
+
+def test_stress_bf16_sampled():
+    inp = wl.make_config(4, 0)
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds, rows=[0, 7], heads=[9])
+    pu.check_lmhead(inp, ds, nodes=[0, 1, 255, 256, 700, 1023])
+    for tau in (0.8, 0.9, 0.95):
+        ds.accept(tau, tau)
+        ds.select()
+        pu.check_accept_and_path(inp, ds, tau_pos=tau, tau_seq=tau)
+
+
+# ---------------------------------------------------------------------------------- edge cases
+
+def _small_bf16(seed, **kw):
+    rng = np.random.default_rng(seed)
+    base = dict(name="edge", dtype="bf16", n_prompts=2, cfg=True, n_heads=4, n_kv_heads=2, head_dim=64, hidden=256,
+                vocab=512, prefix_lens=[70, 70, 5, 5], trees=[wl.grow_tree(rng, 23, 4, 4), wl.grow_tree(rng, 9, 3, 3)],
+                cfg_scale=3.0, temperature=1.0, top_k=50, tau_pos=0.9, tau_seq=0.9, eps_tvd=0.5, token_law="zipf")
+    base.update(kw)
+    return wl.make_inputs(seed=seed, **base)
+
+
+def test_grouped_heads_head_dim_64_and_ragged_tail():
+    inp = _small_bf16(0)
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds)
+    pu.check_lmhead(inp, ds)
+    pu.check_accept_and_path(inp, ds)
+
+
+def test_empty_prefix_and_root_only_tree():
+    rng = np.random.default_rng(1)
+    inp = _small_bf16(1, prefix_lens=[0, 0, 33, 33], trees=[np.array([-1], np.int32), wl.grow_tree(rng, 70, 5, 6)])
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds)
+    pu.check_lmhead(inp, ds)
+    acc, res = pu.check_accept_and_path(inp, ds)
+    assert res.accept_len[0] == 0 and res.terminal[0] == 0
+
+
+def test_wide_tree_spanning_several_query_blocks_and_key_tiles():
+    rng = np.random.default_rng(2)
+    inp = _small_bf16(2, n_prompts=1, prefix_lens=[200, 200], trees=[wl.grow_tree(rng, 150, 7, 8)], head_dim=128,
+                      n_heads=2, n_kv_heads=2)
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds)
+    pu.check_accept_and_path(inp, ds)
+
+
+def test_temperature_and_no_guidance():
+    inp = _small_bf16(3, cfg=False, prefix_lens=[17, 40], temperature=0.7, top_k=0)
+    ds = pu.run_gpu_step(inp)
+    pu.check_lmhead(inp, ds)
+    pu.check_accept_and_path(inp, ds)
+
+
+def test_f32_ragged_batch():
+    rng = np.random.default_rng(4)
+    inp = _small_bf16(4, dtype="f32", head_dim=32, hidden=96, vocab=300, top_k=20,
+                      trees=[wl.grow_tree(rng, 12, 3, 4), wl.grow_tree(rng, 30, 6, 3)])
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds)
+    pu.check_lmhead(inp, ds)
+    pu.check_accept_and_path(inp, ds)
+
+
+def test_argument_validation_enqueues_nothing():
+    inp = wl.make_config(0, 0)
+    ds = binding.DeviceStep(inp)
+    ds.logits.fill_(7.0)
+    with pytest.raises(binding.CascadeError) as e:
+        binding.lmhead_softmax_cfg(ds.ctx, h_cond=ds.h_cond, h_uncond=None, w=ds.w, cfg_scale=1.0, temperature=0.0,
+                                   top_k=0, logits=ds.logits, row_max=ds.row_max, row_thr=ds.row_thr, row_lse=ds.row_lse)
+    assert e.value.status == binding.EINVAL
+    big = torch.zeros((5000, inp.hidden), device="cuda")
+    with pytest.raises(binding.CascadeError) as e:
+        binding.lmhead_softmax_cfg(ds.ctx, h_cond=big, h_uncond=None, w=ds.w, cfg_scale=1.0, temperature=1.0,
+                                   top_k=0, logits=ds.logits, row_max=ds.row_max, row_thr=ds.row_thr, row_lse=ds.row_lse)
+    assert e.value.status == binding.ESHAPE
+    torch.cuda.synchronize()
+    assert torch.all(ds.logits == 7.0)
+
+
+def test_bad_parent_array_is_flagged_not_faulted():
+    inp = wl.make_config(0, 0)
+    inp.parent = inp.parent.copy()
+    inp.parent[5] = 9                      # forward pointer: violates parent[i] < i
+    ds = binding.DeviceStep(inp)
+    ds.lmhead()
+    ds.accept()
+    ds.select()
+    torch.cuda.synchronize()
+    assert ds.ctx.device_status() == binding.ETREE
+    assert ds.ctx.device_status() == binding.OK       # flag is cleared by the query
