@@ -74,6 +74,7 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=1, help="index into the five configurations (default 1: Janus-Pro-7B-shaped)")
     ap.add_argument("--copies", type=int, default=4, help="independent copies of W / KV rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--row-major-w", action="store_true", help="keep the LM-head matrix row-major (default: packed once, as at model load)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -91,14 +92,18 @@ def main() -> int:
     inp = wl.make_config(args.workload, args.seed)
     ds = binding.DeviceStep(inp)
     copies = max(1, args.copies)
-    ws = [ds.w] + [ds.w.clone() for _ in range(copies - 1)]
+    # weights are repacked once into MFMA operand order, as at model load (outside the timed region)
+    packed = inp.dtype == "bf16" and not args.row_major_w
+    layout = binding.W_PACKED32 if packed else binding.W_ROWMAJOR
+    w0 = ds.pack_w() if packed else ds.w
+    ws = [w0] + [w0.clone() for _ in range(copies - 1)]
     kcs = [ds.k_cache] + [ds.k_cache.clone() for _ in range(copies - 1)]
     vcs = [ds.v_cache] + [ds.v_cache.clone() for _ in range(copies - 1)]
 
     def step(i: int) -> None:
         j = i % copies
         ds.k_cache, ds.v_cache = kcs[j], vcs[j]
-        ds.step(w=ws[j])
+        ds.step(w=ws[j], w_layout=layout)
 
     for i in range(args.warmup):
         step(i)
@@ -157,7 +162,8 @@ def main() -> int:
         "config": {"workload": inp.name, "rows": inp.n_rows, "prompts": inp.n_prompts, "tree_nodes": inp.n_nodes,
                    "prefix_len": int(inp.prefix_len.max()), "heads": inp.n_heads, "head_dim": inp.head_dim,
                    "hidden": inp.hidden, "vocab": inp.vocab, "cfg_scale": inp.cfg_scale, "top_k": inp.top_k,
-                   "input_copies_rotated": copies},
+                   "input_copies_rotated": copies,
+                   "lmhead_w_layout": "packed32" if packed else "row_major"},
         "tree_nodes_per_s": inp.n_nodes * args.steps / elapsed,
         "ms_per_step_with_events": ms_per_step_events,
         "kernel_us": kernel_us,

@@ -159,14 +159,28 @@ int tree_verify_attn(cascade_ctx* ctx, const tree_attn_args* args);
  *     h_cond, h_uncond [n_nodes, hidden] dtype, contiguous;  w [vocab, hidden] dtype, contiguous
  *     logits [n_nodes, vocab] float32 (mixed, after temperature, before the filter)
  *     row_max, row_thr, row_lse [n_nodes] float32
- * bf16: hidden must be a multiple of 64 and vocab a multiple of 64.
+ * bf16: hidden must be a multiple of 128 and vocab a multiple of 64.
+ *
+ * Weight layout.  CASCADE_W_ROWMAJOR: w is [vocab, hidden] as above.  CASCADE_W_PACKED32 (bf16
+ * only): w was rewritten once, at model-load time, by cascade_pack_lmhead_w into MFMA operand
+ * order: for every block of 32 vocabulary rows and every 16 hidden columns, 64 x 16 bytes where
+ * entry l holds W[32*block + l%32][16*step + 8*(l/32) .. +7]; blocks of one 32-row group are
+ * consecutive over the hidden dimension.  A wavefront then streams the matrix as contiguous
+ * 1 KiB operand loads.  Same bytes, same values: results do not depend on the layout beyond
+ * float32 summation order.
  */
+typedef enum { CASCADE_W_ROWMAJOR = 0, CASCADE_W_PACKED32 = 1 } cascade_w_layout;
+/* Enqueues the repacking of a bf16 [vocab, hidden] matrix (DEVICE) into w_packed (DEVICE, same
+ * byte size, must not alias w).  vocab % 64 == 0, hidden % 128 == 0. */
+int cascade_pack_lmhead_w(cascade_ctx* ctx, const void* w, int32_t vocab, int32_t hidden, void* w_packed);
+
 typedef struct {
   cascade_dtype dtype;
   int32_t n_nodes, hidden, vocab;
   const void* h_cond;
   const void* h_uncond;       /* nullable => no guidance */
   const void* w;
+  cascade_w_layout w_layout;
   float cfg_scale, temperature;
   int32_t top_k;
   float* logits;

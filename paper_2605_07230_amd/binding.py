@@ -19,10 +19,11 @@ LIB_PATH = os.path.join(_HERE, "libcascade_verify.so")
 F32, BF16 = 0, 1
 WALK_SEQUENTIAL, WALK_LONGEST = 0, 1
 K_ATTN, K_ATTN_MERGE, K_LMHEAD, K_ROW_STATS, K_ACCEPT, K_SELECT = range(6)
+W_ROWMAJOR, W_PACKED32 = 0, 1
 OK, EINVAL, ESHAPE, EDTYPE, ENOMEM, EHIP, ETREE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["cascade_create", "cascade_destroy", "cascade_strerror", "cascade_device_status", "cascade_workspace_bytes",
-           "cascade_set_kernel_timing", "cascade_read_kernel_timing", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path"]
+           "cascade_set_kernel_timing", "cascade_read_kernel_timing", "cascade_pack_lmhead_w", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path"]
 
 _vp, _i32, _i64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
 
@@ -42,7 +43,7 @@ class tree_attn_args(C.Structure):
 
 class lmhead_args(C.Structure):
     _fields_ = [("dtype", C.c_int), ("n_nodes", _i32), ("hidden", _i32), ("vocab", _i32), ("h_cond", _vp),
-                ("h_uncond", _vp), ("w", _vp), ("cfg_scale", _f32), ("temperature", _f32), ("top_k", _i32),
+                ("h_uncond", _vp), ("w", _vp), ("w_layout", C.c_int), ("cfg_scale", _f32), ("temperature", _f32), ("top_k", _i32),
                 ("logits", _vp), ("row_max", _vp), ("row_thr", _vp), ("row_lse", _vp)]
 
 
@@ -87,6 +88,8 @@ def load_library() -> C.CDLL:
     lib.cascade_set_kernel_timing.restype = C.c_int
     lib.cascade_read_kernel_timing.argtypes = [_vp, C.c_int, C.POINTER(C.c_double), C.POINTER(_i32)]
     lib.cascade_read_kernel_timing.restype = C.c_int
+    lib.cascade_pack_lmhead_w.argtypes = [_vp, _vp, _i32, _i32, _vp]
+    lib.cascade_pack_lmhead_w.restype = C.c_int
     for name, st in (("tree_verify_attn", tree_attn_args), ("lmhead_softmax_cfg", lmhead_args),
                      ("cascade_accept", accept_args), ("select_path", select_args)):
         fn = getattr(lib, name)
@@ -177,9 +180,19 @@ def tree_verify_attn(ctx: Context, *, node_off, parent, prefix_len, q, k_tree, v
     _check(ctx.lib.tree_verify_attn(ctx.handle, C.byref(a)))
 
 
-def lmhead_softmax_cfg(ctx: Context, *, h_cond, h_uncond, w, cfg_scale, temperature, top_k, logits, row_max, row_thr, row_lse) -> None:
+def cascade_pack_lmhead_w(ctx: Context, w: torch.Tensor) -> torch.Tensor:
+    """One-time repacking of a bf16 [vocab, hidden] LM-head matrix into MFMA operand order (new tensor)."""
+    assert w.dtype == torch.bfloat16 and w.is_contiguous()
+    out = torch.empty_like(w)
+    _check(ctx.lib.cascade_pack_lmhead_w(ctx.handle, _ptr(w), w.shape[0], w.shape[1], _ptr(out)))
+    return out
+
+
+def lmhead_softmax_cfg(ctx: Context, *, h_cond, h_uncond, w, cfg_scale, temperature, top_k, logits, row_max, row_thr, row_lse,
+                       w_layout: int = W_ROWMAJOR) -> None:
     a = lmhead_args()
     a.dtype = _dtype_code(w)
+    a.w_layout = w_layout
     a.n_nodes, a.hidden, a.vocab = h_cond.shape[0], h_cond.shape[1], w.shape[0]
     a.h_cond, a.h_uncond, a.w = _ptr(h_cond), _ptr(h_uncond), _ptr(w)
     a.cfg_scale, a.temperature, a.top_k = cfg_scale, temperature, top_k
@@ -235,6 +248,7 @@ class DeviceStep:
         self.h_cond = up(inp.h_cond, dt)
         self.h_uncond = up(inp.h_uncond, dt) if inp.h_uncond is not None else None
         self.w = up(inp.w, dt)
+        self.w_packed = None
         self.draft_prob, self.u, self.u_bonus = up(inp.draft_prob), up(inp.u), up(inp.u_bonus)
         N_a, N_c, B = inp.q.shape[0], inp.n_nodes, inp.n_prompts
         self.max_depth = inp.max_depth
@@ -261,8 +275,16 @@ class DeviceStep:
                          out=self.attn_out, lse=self.attn_lse, max_nodes_per_tree=self.max_tree,
                          max_prefix_len=int(self.inp.prefix_len.max()))
 
-    def lmhead(self, w=None):
-        lmhead_softmax_cfg(self.ctx, h_cond=self.h_cond, h_uncond=self.h_uncond, w=self.w if w is None else w,
+    def pack_w(self):
+        """Switch the LM head to the packed weight layout (done once, like at model load)."""
+        self.w_packed = cascade_pack_lmhead_w(self.ctx, self.w)
+        return self.w_packed
+
+    def lmhead(self, w=None, w_layout=None):
+        if w is None:
+            w = self.w_packed if self.w_packed is not None else self.w
+            w_layout = W_PACKED32 if self.w_packed is not None else W_ROWMAJOR
+        lmhead_softmax_cfg(self.ctx, h_cond=self.h_cond, h_uncond=self.h_uncond, w=w, w_layout=w_layout or W_ROWMAJOR,
                            cfg_scale=self.inp.cfg_scale, temperature=self.inp.temperature, top_k=self.inp.top_k,
                            logits=self.logits, row_max=self.row_max, row_thr=self.row_thr, row_lse=self.row_lse)
 
@@ -283,9 +305,9 @@ class DeviceStep:
                     accept_len=self.accept_len, path_nodes=self.path_nodes, emitted=self.emitted,
                     terminal=self.terminal, tvd_used=self.tvd_used)
 
-    def step(self, mode=WALK_SEQUENTIAL, w=None):
+    def step(self, mode=WALK_SEQUENTIAL, w=None, w_layout=None):
         """One whole verification step: the four calls in order on the context's stream."""
         self.attn()
-        self.lmhead(w)
+        self.lmhead(w, w_layout)
         self.accept()
         self.select(mode)

@@ -61,11 +61,14 @@ int cascade_create(cascade_ctx** out, const cascade_limits* lim, void* hip_strea
   const size_t cap = (size_t)256 << 20;
   if (attn > cap) attn = cap;
   c->attn_ws_bytes = align_up(attn, 256);
-  c->ws_bytes = 256 + c->attn_ws_bytes;
+  // packed hidden states: two operands (cond, uncond), rows rounded up to 64, 2 bytes per element
+  c->hpack_ws_bytes = align_up((size_t)2 * ((lim->max_nodes_total + 63) / 64 * 64) * lim->hidden * 2, 256);
+  c->ws_bytes = 256 + c->attn_ws_bytes + c->hpack_ws_bytes;
   e = hipMalloc((void**)&c->ws, c->ws_bytes);
   if (e != hipSuccess) { delete c; (void)hipGetLastError(); return CASCADE_ENOMEM; }
   c->dev_status = (int*)c->ws;
   c->attn_ws = c->ws + 256;
+  c->hpack_ws = c->attn_ws + c->attn_ws_bytes;
   e = hipMemsetAsync(c->ws, 0, 256, c->stream);
   if (e != hipSuccess) { (void)hipFree(c->ws); delete c; return hip_fail(e); }
   *out = c;
@@ -182,15 +185,25 @@ int lmhead_softmax_cfg(cascade_ctx* ctx, const lmhead_args* a) {
   const cascade_limits& L = ctx->lim;
   if (a->n_nodes > L.max_nodes_total || a->hidden > L.hidden || a->vocab > L.vocab || a->vocab > CASCADE_MAX_VOCAB)
     return CASCADE_ESHAPE;
+  if (a->w_layout != CASCADE_W_ROWMAJOR && a->w_layout != CASCADE_W_PACKED32) return CASCADE_EINVAL;
   if (a->dtype == CASCADE_BF16) {
     if ((a->hidden % 128) || (a->vocab % 64)) return CASCADE_ESHAPE;
   } else {
     if (a->hidden > 8192) return CASCADE_ESHAPE;
+    if (a->w_layout != CASCADE_W_ROWMAJOR) return CASCADE_EDTYPE;
   }
   if (a->n_nodes == 0) return CASCADE_OK;
   hipError_t e = (a->dtype == CASCADE_BF16) ? launch_lmhead_bf16(ctx, a) : launch_lmhead_f32(ctx, a);
   if (e != hipSuccess) return hip_fail(e);
   e = launch_row_stats(ctx, a);
+  return e == hipSuccess ? CASCADE_OK : hip_fail(e);
+}
+
+int cascade_pack_lmhead_w(cascade_ctx* ctx, const void* w, int32_t vocab, int32_t hidden, void* w_packed) {
+  if (!ctx || !w || !w_packed || w == w_packed) return CASCADE_EINVAL;
+  if (vocab <= 0 || hidden <= 0) return CASCADE_EINVAL;
+  if ((vocab % 64) || (hidden % 128)) return CASCADE_ESHAPE;
+  hipError_t e = launch_pack_w(ctx, w, vocab, hidden, w_packed);
   return e == hipSuccess ? CASCADE_OK : hip_fail(e);
 }
 

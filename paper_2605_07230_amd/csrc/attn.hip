@@ -386,24 +386,32 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
   }
 }
 
-// one block of D threads per output row: log-sum-exp merge of the split partials
+// log-sum-exp merge of the split partials: D/4 lanes per output row (a float4 each), 256 threads
 template <int D>
-__global__ __launch_bounds__(D) void attn_merge_kernel(AttnParams p) {
-  const int64_t row = blockIdx.x;
-  const int d = threadIdx.x;
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnParams p) {
+  constexpr int LPR = D / 4;             // lanes per row
+  constexpr int RPB = 256 / LPR;         // rows per block
+  const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / LPR;
+  const int d4 = threadIdx.x % LPR;
+  if (row >= p.n_rows_total) return;
   float m = -INFINITY;
   for (int c = 0; c < p.n_split; ++c) m = fmaxf(m, p.ws_ml[((int64_t)c * p.n_rows_total + row) * 2]);
-  float o = 0.f, l = 0.f;
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  float l = 0.f;
   for (int c = 0; c < p.n_split; ++c) {
     const float* ml = p.ws_ml + ((int64_t)c * p.n_rows_total + row) * 2;
     const float mc = ml[0];
     if (mc == -INFINITY) continue;
     const float w = exp2f(mc - m);
     l += w * ml[1];
-    o += w * p.ws_o[((int64_t)c * p.n_rows_total + row) * D + d];
+    o += w * *(const f32x4*)(p.ws_o + ((int64_t)c * p.n_rows_total + row) * D + 4 * d4);
   }
-  ((uint16_t*)p.out)[row * D + d] = f32_to_bf16_bits(o / l);
-  if (d == 0 && p.lse) p.lse[row] = m * LN2 + logf(l);
+  const float inv = 1.f / l;
+  uint2 packed;
+  packed.x = pack_bf16x2(o[0] * inv, o[1] * inv);
+  packed.y = pack_bf16x2(o[2] * inv, o[3] * inv);
+  *(uint2*)((uint16_t*)p.out + row * D + 4 * d4) = packed;
+  if (d4 == 0 && p.lse) p.lse[row] = m * LN2 + logf(l);
 }
 
 AttnParams make_params(cascade_ctx* ctx, const tree_attn_args* a) {
@@ -444,7 +452,7 @@ hipError_t launch_bf16_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
       hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, true>), grid, dim3(256), 0, st, p);
     }
     KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
-    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3(p.n_rows_total), dim3(D), 0, st, p);
+    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
   } else {
     KernelTimer t(ctx, CASCADE_K_ATTN);
     hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, false>), grid, dim3(256), 0, st, p);

@@ -17,6 +17,8 @@ struct cascade_ctx {
   int* dev_status;        // one int at the start of ws: sticky precondition flag
   char* attn_ws;          // split-KV partials
   size_t attn_ws_bytes;
+  char* hpack_ws;         // hidden states repacked into MFMA operand order, cond then uncond
+  size_t hpack_ws_bytes;
   // optional per-kernel timing with HIP events on the ctx stream (cascade_set_kernel_timing)
   bool timing;
   hipEvent_t* ev;         // [CASCADE_K_COUNT][TIMING_RING][2], created on first enable
@@ -54,6 +56,7 @@ hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a);
 hipError_t launch_lmhead_f32(cascade_ctx* ctx, const lmhead_args* a);
 hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a);
 hipError_t launch_row_stats(cascade_ctx* ctx, const lmhead_args* a);
+hipError_t launch_pack_w(cascade_ctx* ctx, const void* w, int vocab, int hidden, void* w_packed);
 hipError_t launch_accept(cascade_ctx* ctx, const accept_args* a);
 hipError_t launch_select(cascade_ctx* ctx, const select_args* a);
 

@@ -20,6 +20,8 @@ struct LmParams {
   float* row_max;
   float* row_thr;
   float* row_lse;
+  const uint4* hp_cond;     // packed hidden states (MFMA operand order), when the packed path runs
+  const uint4* hp_uncond;
   int n_nodes, hidden, vocab;
   int n_mchunks;
   float cfg_scale, temperature;
@@ -158,6 +160,105 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmParams p) {
   }
 }
 
+// ------------------------------------------------------------------------- bf16, packed operands
+// Operand order: for a block of 32 rows rb and a 16-wide k step ks, 64 x 16 bytes where entry
+// l = (r32, half) holds src[32*rb + r32][16*ks + 8*half .. +7]; the ks blocks of one rb follow
+// each other.  One wave-wide 16-byte load per MFMA operand, 1 KiB contiguous.
+__global__ __launch_bounds__(256) void pack32_kernel(const uint16_t* __restrict__ src, uint4* __restrict__ dst, int rows, int K) {
+  const int lane = threadIdx.x & 63, r32 = lane & 31, half = lane >> 5;
+  const int ks = blockIdx.x * 4 + (threadIdx.x >> 6), rb = blockIdx.y;
+  if (ks >= K / 16) return;
+  const int row = 32 * rb + r32;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row < rows) v = *(const uint4*)(src + (int64_t)row * K + 16 * ks + 8 * half);
+  dst[((int64_t)rb * (K / 16) + ks) * 64 + lane] = v;
+}
+
+template <bool CFG>
+__global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
+  constexpr int NA = CFG ? 4 : 2;
+  extern __shared__ float red[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r32 = lane & 31, half = lane >> 5;
+  const int K = p.hidden, KS = K / 16;
+
+  int logical = blockIdx.x;
+  const int nwg = gridDim.x;
+  if ((nwg & 7) == 0) logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
+  const int ntile = logical / p.n_mchunks, mc = logical % p.n_mchunks;
+  const int v0 = ntile * 64, node0 = mc * 64;
+
+  const uint4* ap[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const uint4* base = (i < 2) ? p.hp_cond : p.hp_uncond;
+    ap[i] = base + ((int64_t)(mc * 2 + (i & 1)) * KS) * 64 + lane;
+  }
+  const uint4* bp[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) bp[j] = (const uint4*)p.w + ((int64_t)(ntile * 2 + j) * KS) * 64 + lane;
+
+  f32x16 acc[NA][2];
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int n_slices = (K / 128 - wave + 3) / 4;
+  const int n_groups = 2 * n_slices;
+  auto ks_of = [&](int gi) { return (wave + 4 * (gi >> 1)) * 8 + 4 * (gi & 1); };   // first k16 step of the group
+  auto load_group = [&](Group<CFG>& G, int ks) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) G.a[s][i].u = ap[i][(int64_t)(ks + s) * 64];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) G.b[s][j].u = bp[j][(int64_t)(ks + s) * 64];
+    }
+  };
+  auto compute_group = [&](const Group<CFG>& G) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int i = 0; i < NA; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(G.a[s][i].v, G.b[s][j].v, acc[i][j], 0, 0, 0);
+  };
+  Group<CFG> g0, g1;
+  if (n_groups > 0) load_group(g0, ks_of(0));
+  for (int gi = 0; gi < n_groups; gi += 2) {
+    load_group(g1, ks_of(gi + 1));
+    compute_group(g0);
+    if (gi + 2 < n_groups) load_group(g0, ks_of(gi + 2));
+    compute_group(g1);
+  }
+
+  constexpr int NACC = NA * 2;
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[((wave * NACC + i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+  __syncthreads();
+  const int nbk = wave >> 1, nb = wave & 1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float c = 0.f, u = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      c += red[((w * NACC + nbk * 2 + nb) * 16 + r) * 64 + lane];
+      if (CFG) u += red[((w * NACC + (2 + nbk) * 2 + nb) * 16 + r) * 64 + lane];
+    }
+    const float gmix = CFG ? u + p.cfg_scale * (c - u) : c;
+    const int node = node0 + 32 * nbk + 8 * (r >> 2) + 4 * half + (r & 3);
+    if (node < p.n_nodes) p.logits[(int64_t)node * p.vocab + v0 + 32 * nb + r32] = gmix / p.temperature;
+  }
+}
+
 // ------------------------------------------------------------------------------------ row stats
 // One workgroup of 1024 threads per row; the row lives in registers (VPT values per thread).
 // row_max, exact k-th largest (bitwise radix select on order-preserving integer keys), and
@@ -242,6 +343,8 @@ LmParams make_params(const lmhead_args* a) {
   p.row_max = a->row_max;
   p.row_thr = a->row_thr;
   p.row_lse = a->row_lse;
+  p.hp_cond = nullptr;
+  p.hp_uncond = nullptr;
   p.n_nodes = a->n_nodes;
   p.hidden = a->hidden;
   p.vocab = a->vocab;
@@ -264,26 +367,47 @@ hipError_t launch_lmhead_f32(cascade_ctx* ctx, const lmhead_args* a) {
   return hipGetLastError();
 }
 
+template <bool CFG, bool PACKED>
+hipError_t launch_bf16_gemm(cascade_ctx* ctx, const LmParams& p, int grid) {
+  const size_t smem = (size_t)4 * (CFG ? 8 : 4) * 16 * 64 * sizeof(float);
+  auto kern = PACKED ? lmhead_bf16_packed_kernel<CFG> : lmhead_bf16_kernel<CFG>;
+  static bool attr_done = false;   // one flag per template instance
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  KernelTimer t(ctx, CASCADE_K_LMHEAD);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, ctx->stream, p);
+  return hipGetLastError();
+}
+
 hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
-  hipStream_t stream = ctx->stream;
   LmParams p = make_params(a);
   const int grid = (a->vocab / 64) * p.n_mchunks;
-  hipError_t e;
-  if (a->h_uncond) {
-    const size_t smem = 4 * 8 * 16 * 64 * sizeof(float);
-    static bool attr_done = false;
-    if (!attr_done) {
-      e = hipFuncSetAttribute((const void*)lmhead_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-      if (e != hipSuccess) return e;
-      attr_done = true;
-    }
-    KernelTimer t(ctx, CASCADE_K_LMHEAD);
-    hipLaunchKernelGGL(lmhead_bf16_kernel<true>, dim3(grid), dim3(256), smem, stream, p);
-  } else {
-    const size_t smem = 4 * 4 * 16 * 64 * sizeof(float);
-    KernelTimer t(ctx, CASCADE_K_LMHEAD);
-    hipLaunchKernelGGL(lmhead_bf16_kernel<false>, dim3(grid), dim3(256), smem, stream, p);
+  const bool cfg = a->h_uncond != nullptr;
+  if (a->w_layout == CASCADE_W_PACKED32) {
+    // repack this step's hidden states into operand order (rows rounded up to 64 per operand)
+    const int rblocks = p.n_mchunks * 2;
+    const size_t per = (size_t)rblocks * 32 * a->hidden * 2;
+    if (per * 2 > ctx->hpack_ws_bytes) return hipErrorInvalidValue;
+    uint4* hc = (uint4*)ctx->hpack_ws;
+    uint4* hu = (uint4*)(ctx->hpack_ws + per);
+    dim3 pgrid((a->hidden / 16 + 3) / 4, rblocks);
+    hipLaunchKernelGGL(pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_cond, hc, a->n_nodes, a->hidden);
+    if (cfg) hipLaunchKernelGGL(pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_uncond, hu, a->n_nodes, a->hidden);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    p.hp_cond = hc;
+    p.hp_uncond = hu;
+    return cfg ? launch_bf16_gemm<true, true>(ctx, p, grid) : launch_bf16_gemm<false, true>(ctx, p, grid);
   }
+  return cfg ? launch_bf16_gemm<true, false>(ctx, p, grid) : launch_bf16_gemm<false, false>(ctx, p, grid);
+}
+
+hipError_t launch_pack_w(cascade_ctx* ctx, const void* w, int vocab, int hidden, void* w_packed) {
+  dim3 grid((hidden / 16 + 3) / 4, vocab / 32);
+  hipLaunchKernelGGL(pack32_kernel, grid, dim3(256), 0, ctx->stream, (const uint16_t*)w, (uint4*)w_packed, vocab, hidden);
   return hipGetLastError();
 }
 

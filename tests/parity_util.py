@@ -18,9 +18,12 @@ def max_rel_err(got, ref):
     return float(np.abs(got[finite] - ref[finite]).max() / max(np.abs(ref[finite]).max(), 1e-30))
 
 
-def run_gpu_step(inp, mode=binding.WALK_SEQUENTIAL):
-    print(f"[gpu step] {inp.name} dtype={inp.dtype} rows={inp.n_rows} nodes={inp.n_nodes} mode={mode}", flush=True)
+def run_gpu_step(inp, mode=binding.WALK_SEQUENTIAL, packed_w=False):
+    print(f"[gpu step] {inp.name} dtype={inp.dtype} rows={inp.n_rows} nodes={inp.n_nodes} mode={mode} "
+          f"packed_w={packed_w}", flush=True)
     ds = binding.DeviceStep(inp)
+    if packed_w:
+        ds.pack_w()
     ds.step(mode)
     torch.cuda.synchronize()
     assert ds.ctx.device_status() == binding.OK

@@ -50,10 +50,10 @@ def test_tiny_f32_variants(variant):
         assert acc.n_conv.sum() >= 3
 
 
-@pytest.mark.parametrize("seed", [0, 3])
-def test_janus_shaped_bf16_whole_step(seed):
+@pytest.mark.parametrize("seed,packed", [(0, False), (3, False), (0, True), (5, True)])
+def test_janus_shaped_bf16_whole_step(seed, packed):
     inp = wl.make_config(1, seed)
-    ds = pu.run_gpu_step(inp)
+    ds = pu.run_gpu_step(inp, packed_w=packed)
     pu.check_attention(inp, ds, heads=[0, 5, 31])
     pu.check_lmhead(inp, ds)
     pu.check_accept_and_path(inp, ds)
@@ -72,7 +72,7 @@ def test_janus_shaped_threshold_pairs():
 
 def test_lumina_shaped_bf16_sampled():
     inp = wl.make_config(2, 0)
-    ds = pu.run_gpu_step(inp)
+    ds = pu.run_gpu_step(inp, packed_w=True)
     pu.check_attention(inp, ds, heads=[3, 17])
     pu.check_lmhead(inp, ds, nodes=[0, 1, 7, 30, 59])
     pu.check_accept_and_path(inp, ds)
@@ -80,7 +80,7 @@ def test_lumina_shaped_bf16_sampled():
 
 def test_batched_ragged_bf16():
     inp = wl.make_config(3, 0)
-    ds = pu.run_gpu_step(inp)
+    ds = pu.run_gpu_step(inp, packed_w=True)
     pu.check_attention(inp, ds, rows=[0, 1, 6, 15], heads=[0, 13])
     nodes = np.unique(np.concatenate([inp.node_off[:-1], inp.node_off[1:] - 1, np.arange(0, inp.n_nodes, 37)]))
     pu.check_lmhead(inp, ds, nodes=nodes)
@@ -89,7 +89,7 @@ def test_batched_ragged_bf16():
 
 def test_stress_bf16_sampled():
     inp = wl.make_config(4, 0)
-    ds = pu.run_gpu_step(inp)
+    ds = pu.run_gpu_step(inp, packed_w=True)
     pu.check_attention(inp, ds, rows=[0, 7], heads=[9])
     pu.check_lmhead(inp, ds, nodes=[0, 1, 255, 256, 700, 1023])
     for tau in (0.8, 0.9, 0.95):
@@ -136,11 +136,21 @@ def test_wide_tree_spanning_several_query_blocks_and_key_tiles():
     pu.check_accept_and_path(inp, ds)
 
 
-def test_temperature_and_no_guidance():
+@pytest.mark.parametrize("packed", [False, True])
+def test_temperature_and_no_guidance(packed):
     inp = _small_bf16(3, cfg=False, prefix_lens=[17, 40], temperature=0.7, top_k=0)
-    ds = pu.run_gpu_step(inp)
+    ds = pu.run_gpu_step(inp, packed_w=packed)
     pu.check_lmhead(inp, ds)
     pu.check_accept_and_path(inp, ds)
+
+
+def test_packed_and_row_major_weights_agree_bitwise_on_statistics():
+    inp = _small_bf16(6, n_prompts=1, prefix_lens=[9, 9], trees=[wl.grow_tree(np.random.default_rng(6), 70, 5, 6)])
+    a = pu.run_gpu_step(inp)
+    b = pu.run_gpu_step(inp, packed_w=True)
+    # same products, same per-wave k order: the two layouts give identical logits
+    assert torch.equal(a.logits, b.logits) and torch.equal(a.row_thr, b.row_thr)
+    assert torch.equal(a.emitted, b.emitted)
 
 
 def test_f32_ragged_batch():
