@@ -1,18 +1,22 @@
-// cascade_accept and select_path kernels for gfx950.
+// cascade_accept kernels for gfx950 (Sec. 4.1 cosine similarity of target hidden states; Eq. 1
+// interchangeable set; Eq. 2 convergence set; Eq. 3 aggregated mass).
 //
-// cascade_accept: one wavefront per tree node.  The wave finds the node's siblings and children
-// by scanning the parent array with ballots, computes the cosine similarity of the target hidden
-// states against each of them (Sec. 4.1), forms the interchangeable set (Eq. 1) and the
-// convergent set (Eq. 2), and sums the probability mass their distinct tokens carry under the
-// distribution that verifies the node (Eq. 3).
-//
-// select_path: one workgroup per prompt.  Wave 0 runs the serial walk of Alg. 2 over those
-// scalars (budget-gated aggregation, then Alg. 1's test r*p < q); the workgroup then draws the
-// correction / bonus token by inverse CDF over the terminal node's distribution with the
-// rejected siblings' tokens removed.
+// Kernel 1, one workgroup per parent node p: the Gram matrix of the rows [F_p, F_child_1 ..
+// F_child_k] gives every cosine the children of p need at once — sibling/sibling (Eq. 1) and
+// parent/child (Eq. 2).  For bf16 hidden states it is a dense contraction and runs on
+// v_mfma_f32_16x16x32_bf16 (16 x 16 row blocks, operands loaded straight from global memory as
+// 16-byte k-contiguous pieces); for f32 it is plain wave-wide dot products.  The workgroup then
+// forms I_a for each child a, sums the mass of its distinct tokens under p's distribution, and
+// writes q_tok, m_int, n_int, cos_parent and a 64-bit membership mask of I_a (by sibling rank).
+// Kernel 2, one wavefront per node a: C_a from cos_parent of a's children, then m_conv over the
+// distinct tokens not already counted (a's own token, tokens of I_a), and n_conv.
 #include "common.h"
 
 namespace {
+
+constexpr int MAXW = CASCADE_MAX_WIDTH;   // children per node
+constexpr int GN = MAXW + 1;              // rows of the Gram matrix: parent + children
+constexpr int GP = GN + 1;                // LDS pitch
 
 // probability of vocabulary entry t under a row's filtered softmax
 __device__ __forceinline__ float prob_of(const float* logits_row, float thr, float lse, int t) {
@@ -20,119 +24,239 @@ __device__ __forceinline__ float prob_of(const float* logits_row, float thr, flo
   return gv >= thr ? __expf(gv - lse) : 0.f;
 }
 
-template <typename T>
-struct DotAcc;
-
-// dot(a,b), |b|^2 over one hidden-state row pair, whole wave cooperating
-template <>
-struct DotAcc<uint16_t> {
-  static __device__ __forceinline__ void run(const uint16_t* a, const uint16_t* b, int h, int lane, float& ab, float& bb) {
-    float s_ab = 0.f, s_bb = 0.f;
-    for (int k = lane * 8; k < h; k += 64 * 8) {   // h is a multiple of 8
-      const uint4 ua = *(const uint4*)(a + k), ub = *(const uint4*)(b + k);
-      const uint32_t wa[4] = {ua.x, ua.y, ua.z, ua.w}, wb[4] = {ub.x, ub.y, ub.z, ub.w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float a0 = __uint_as_float(wa[i] << 16), a1 = __uint_as_float(wa[i] & 0xffff0000u);
-        const float b0 = __uint_as_float(wb[i] << 16), b1 = __uint_as_float(wb[i] & 0xffff0000u);
-        s_ab = fmaf(a0, b0, s_ab);
-        s_ab = fmaf(a1, b1, s_ab);
-        s_bb = fmaf(b0, b0, s_bb);
-        s_bb = fmaf(b1, b1, s_bb);
-      }
-    }
-    ab = wave_sum(s_ab);
-    bb = wave_sum(s_bb);
-  }
-};
-template <>
-struct DotAcc<float> {
-  static __device__ __forceinline__ void run(const float* a, const float* b, int h, int lane, float& ab, float& bb) {
-    float s_ab = 0.f, s_bb = 0.f;
-    for (int k = lane; k < h; k += 64) {
-      const float av = a[k], bv = b[k];
-      s_ab = fmaf(av, bv, s_ab);
-      s_bb = fmaf(bv, bv, s_bb);
-    }
-    ab = wave_sum(s_ab);
-    bb = wave_sum(s_bb);
-  }
-};
-
 __device__ __forceinline__ float cos_from(float ab, float aa, float bb) {
   return (aa > 0.f && bb > 0.f) ? ab / (sqrtf(aa) * sqrtf(bb)) : 0.f;
 }
 
+__device__ __forceinline__ float dot_rows(const float* a, const float* b, int h, int lane) {
+  float s = 0.f;
+  for (int k = lane; k < h; k += 64) s = fmaf(a[k], b[k], s);
+  return wave_sum(s);
+}
+__device__ __forceinline__ float dot_rows(const uint16_t* a, const uint16_t* b, int h, int lane) {
+  float s = 0.f;
+  for (int k = lane * 8; k < h; k += 64 * 8) {   // h is a multiple of 8
+    const uint4 ua = *(const uint4*)(a + k), ub = *(const uint4*)(b + k);
+    const uint32_t wa[4] = {ua.x, ua.y, ua.z, ua.w}, wb[4] = {ub.x, ub.y, ub.z, ub.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s = fmaf(__uint_as_float(wa[i] << 16), __uint_as_float(wb[i] << 16), s);
+      s = fmaf(__uint_as_float(wa[i] & 0xffff0000u), __uint_as_float(wb[i] & 0xffff0000u), s);
+    }
+  }
+  return wave_sum(s);
+}
+
+union Frag8 {
+  bf16x8 v;
+  uint4 u;
+};
+
+// C[16x16] += A[16 rows][k] * B[16 rows][k]^T over k in [k0, k1), (k1 - k0) a multiple of 32;
+// rowa / rowb are this lane's row pointers, g its 8-wide k group
+__device__ __forceinline__ f32x4 gram_tile(const uint16_t* rowa, const uint16_t* rowb, bool same, int k0, int k1, int g) {
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  int k = k0;
+  for (; k + 128 <= k1; k += 128) {   // 4 MFMA steps per iteration, loads issued together
+    Frag8 fa[4], fb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) fa[s].u = *(const uint4*)(rowa + k + 32 * s + 8 * g);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) fb[s].u = same ? fa[s].u : *(const uint4*)(rowb + k + 32 * s + 8 * g);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[s].v, fb[s].v, acc, 0, 0, 0);
+  }
+  for (; k < k1; k += 32) {
+    Frag8 fa, fb;
+    fa.u = *(const uint4*)(rowa + k + 8 * g);
+    fb.u = same ? fa.u : *(const uint4*)(rowb + k + 8 * g);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, fb.v, acc, 0, 0, 0);
+  }
+  return acc;
+}
+
 template <typename T>
-__global__ __launch_bounds__(256) void accept_kernel(accept_args a, int* dev_status) {
-  __shared__ int tok_i[4][CASCADE_MAX_WIDTH];
-  __shared__ int tok_c[4][CASCADE_MAX_WIDTH];
+__global__ __launch_bounds__(256) void accept_gram_kernel(accept_args a, unsigned long long* imask, int* dev_status) {
+  __shared__ float gfull[GN * GP];        // Gram matrix; for MFMA tiles only blocks (bi <= bj) are filled
+  __shared__ float gq[4][256];            // K-quarter partial tiles when there is a single 16 x 16 block
+  __shared__ int s_child[MAXW];
+  __shared__ int s_tok[MAXW];
+  __shared__ int s_k;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.y, p = blockIdx.x;
+  const int lo = a.node_off[b], Tn = a.node_off[b + 1] - lo;
+  if (p >= Tn) return;
+  const int h = a.hidden;
+  const T* H = (const T*)a.h_cond;
+
+  if (wave == 0) {   // ordered list of p's children
+    int k = 0;
+    for (int base = (p + 1) & ~63; base < Tn; base += 64) {
+      const int j = base + lane;
+      const bool is = j < Tn && j > p && a.parent[lo + j] == p;
+      const unsigned long long m = __ballot(is);
+      if (is) {
+        const int idx = k + __popcll(m & ((1ull << lane) - 1ull));
+        if (idx < MAXW) { s_child[idx] = j; s_tok[idx] = a.token[lo + j]; }
+      }
+      k += __popcll(m);
+    }
+    if (k > MAXW) {
+      if (lane == 0) atomicOr(dev_status, CASCADE_FLAG_WIDTH);
+      k = MAXW;
+    }
+    if (lane == 0) s_k = k;
+  }
+  __syncthreads();
+  const int k = s_k;
+  if (k == 0) return;
+  const int n = k + 1, nb = (n + 15) >> 4;
+  auto row_of = [&](int r) -> const T* { return H + (int64_t)(lo + (r == 0 ? p : s_child[r - 1])) * h; };
+
+  bool mfma_done = false;
+  if constexpr (sizeof(T) == 2) {
+    if ((h & 127) == 0) {
+      mfma_done = true;
+      const int l16 = lane & 15, g = lane >> 4;
+      if (nb == 1) {
+        // one block: the four waves split the hidden dimension, partial tiles summed in a fixed order
+        const uint16_t* ra = (const uint16_t*)row_of(min(l16, n - 1));
+        const int kq = h / 4;   // a multiple of 32
+        const f32x4 acc = gram_tile(ra, ra, true, wave * kq, (wave + 1) * kq, g);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) gq[wave][(4 * g + r) * 16 + l16] = acc[r];
+        __syncthreads();
+        const int i = tid >> 4, j = tid & 15;
+        if (i < n && j < n) gfull[i * GP + j] = ((gq[0][tid] + gq[1][tid]) + gq[2][tid]) + gq[3][tid];
+      } else {
+        // several blocks: block pairs (bi <= bj) are shared out over the waves, full hidden dimension each
+        const int npairs = nb * (nb + 1) / 2;
+        for (int pi = wave; pi < npairs; pi += 4) {
+          int bi = 0, rem = pi;
+          while (rem >= nb - bi) { rem -= nb - bi; ++bi; }
+          const int bj = bi + rem;
+          const uint16_t* ra = (const uint16_t*)row_of(min(16 * bi + l16, n - 1));
+          const uint16_t* rb = (const uint16_t*)row_of(min(16 * bj + l16, n - 1));
+          const f32x4 acc = gram_tile(ra, rb, bi == bj, 0, h, g);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int i = 16 * bi + 4 * g + r, j = 16 * bj + l16;
+            if (i < n && j < n) gfull[i * GP + j] = acc[r];
+          }
+        }
+      }
+    }
+  }
+  if (!mfma_done) {
+    const int npairs = n * (n + 1) / 2;
+    for (int pi = wave; pi < npairs; pi += 4) {
+      int i = 0, rem = pi;
+      while (rem >= n - i) { rem -= n - i; ++i; }
+      const int j = i + rem;
+      const float d = dot_rows(row_of(i), row_of(j), h, lane);
+      if (lane == 0) { gfull[i * GP + j] = d; gfull[j * GP + i] = d; }
+    }
+  }
+  __syncthreads();
+  // entries (i, j) with i in a later 16-row block than j were produced as (j, i)
+  auto G = [&](int i, int j) -> float { return ((i >> 4) > (j >> 4)) ? gfull[j * GP + i] : gfull[i * GP + j]; };
+
+  const float* Lp = a.logits + (int64_t)(lo + p) * a.vocab;
+  const float thr = a.row_thr[lo + p], lse = a.row_lse[lo + p];
+  const float g00 = G(0, 0);
+  for (int i = wave; i < k; i += 4) {   // child i is row i + 1
+    const int node = s_child[i];
+    const int ta = s_tok[i];
+    const bool tok_ok = ta >= 0 && ta < a.vocab;
+    const float gii = G(i + 1, i + 1);
+    bool member = false;
+    int tj = -1;
+    if (lane < k && lane != i) {
+      tj = s_tok[lane];
+      member = cos_from(G(i + 1, lane + 1), gii, G(lane + 1, lane + 1)) >= a.tau_pos;
+    }
+    const unsigned long long mask = __ballot(member);
+    float mass = 0.f;
+    if (member && tj != ta && tj >= 0 && tj < a.vocab) {
+      bool dup = false;
+      for (unsigned long long m = mask & ((1ull << lane) - 1ull); m; m &= m - 1) dup |= (s_tok[__ffsll((long long)m) - 1] == tj);
+      if (!dup) mass = prob_of(Lp, thr, lse, tj);
+    }
+    mass = wave_sum(mass);
+    if (lane == 0) {
+      if (!tok_ok) atomicOr(dev_status, CASCADE_FLAG_TOKEN);
+      const int64_t gi = lo + node;
+      a.q_tok[gi] = tok_ok ? prob_of(Lp, thr, lse, ta) : 0.f;
+      a.m_int[gi] = mass;
+      a.n_int[gi] = __popcll(mask);
+      a.cos_parent[gi] = cos_from(G(0, i + 1), g00, gii);
+      imask[gi] = mask;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void accept_conv_kernel(accept_args a, const unsigned long long* imask, int* dev_status) {
+  __shared__ int tok_i[4][MAXW];
+  __shared__ int tok_c[4][MAXW];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.y;
   const int lo = a.node_off[b], Tn = a.node_off[b + 1] - lo;
   const int node = blockIdx.x * 4 + wave;
   if (node >= Tn) return;
   const int64_t gi = lo + node;
-  const int h = a.hidden;
-  const T* H = (const T*)a.h_cond;
-  int par = a.parent[gi];
+  const int par = a.parent[gi];
   if (node == 0 || par < 0 || par >= node) {
+    // roots, and nodes whose parent pointer is unusable (no workgroup of kernel 1 owns them)
     if (lane == 0) {
       if (node > 0 || par != -1) atomicOr(dev_status, CASCADE_FLAG_PARENT);
-      a.q_tok[gi] = 0.f; a.m_int[gi] = 0.f; a.m_conv[gi] = 0.f; a.cos_parent[gi] = 0.f;
-      a.n_int[gi] = 0; a.n_conv[gi] = 0;
+      a.q_tok[gi] = 0.f; a.m_int[gi] = 0.f; a.cos_parent[gi] = 0.f; a.n_int[gi] = 0;
+      a.m_conv[gi] = 0.f; a.n_conv[gi] = 0;
     }
     return;
   }
   const int ta = a.token[gi];
-  const bool tok_ok = ta >= 0 && ta < a.vocab;
-  if (!tok_ok && lane == 0) atomicOr(dev_status, CASCADE_FLAG_TOKEN);
-  const float* Lp = a.logits + (int64_t)(lo + par) * a.vocab;
-  const float thr = a.row_thr[lo + par], lse = a.row_lse[lo + par];
-  const T* Ha = H + gi * h;
-  float aa, dummy;
-  DotAcc<T>::run(Ha, Ha, h, lane, dummy, aa);
-  float ab, bb;
-  DotAcc<T>::run(Ha, H + (int64_t)(lo + par) * h, h, lane, ab, bb);
-  const float cpar = cos_from(ab, aa, bb);
-
-  int n_i = 0, n_c = 0;
-  bool overflow = false;
+  const unsigned long long im = imask[gi];
+  const int n_i = __popcll(im);
+  int n_c = 0, rank = 0, myrank = -1;
   for (int base = 0; base < Tn; base += 64) {
     const int j = base + lane;
     const int pj = j < Tn ? a.parent[lo + j] : -2;
-    unsigned long long sib = __ballot(pj == par && j != node);
-    unsigned long long chi = __ballot(pj == node);
-    while (sib) {
-      const int bn = base + __ffsll((long long)sib) - 1;
-      sib &= sib - 1;
-      DotAcc<T>::run(Ha, H + (int64_t)(lo + bn) * h, h, lane, ab, bb);
-      if (cos_from(ab, aa, bb) >= a.tau_pos) {
-        if (n_i < CASCADE_MAX_WIDTH) { if (lane == 0) tok_i[wave][n_i] = a.token[lo + bn]; ++n_i; }
-        else overflow = true;
-      }
+    // siblings in rank order (the rank counts every child of par, this node included)
+    const bool sib = pj == par && j > par;
+    const unsigned long long sm = __ballot(sib);
+    if (sib) {
+      const int r = rank + __popcll(sm & ((1ull << lane) - 1ull));
+      // position inside I_a = number of member ranks below r
+      if (r < MAXW && ((im >> r) & 1ull)) tok_i[wave][__popcll(im & ((1ull << r) - 1ull))] = a.token[lo + j];
     }
-    while (chi) {
-      const int bn = base + __ffsll((long long)chi) - 1;
-      chi &= chi - 1;
-      DotAcc<T>::run(Ha, H + (int64_t)(lo + bn) * h, h, lane, ab, bb);
-      if (cos_from(ab, aa, bb) >= a.tau_seq) {
-        if (n_c < CASCADE_MAX_WIDTH) { if (lane == 0) tok_c[wave][n_c] = a.token[lo + bn]; ++n_c; }
-        else overflow = true;
-      }
+    if (node >= base && node < base + 64) myrank = rank + __popcll(sm & ((1ull << (node - base)) - 1ull));
+    rank += __popcll(sm);
+    // children of this node whose features stay close to it (Eq. 2)
+    const bool conv = pj == node && j > node && a.cos_parent[lo + j] >= a.tau_seq;
+    const unsigned long long cm = __ballot(conv);
+    if (conv) {
+      const int idx = n_c + __popcll(cm & ((1ull << lane) - 1ull));
+      if (idx < MAXW) tok_c[wave][idx] = a.token[lo + j];
     }
+    n_c += __popcll(cm);
   }
-  if (overflow && lane == 0) atomicOr(dev_status, CASCADE_FLAG_WIDTH);
+  if (myrank >= MAXW) {
+    // beyond the width limit: kernel 1 did not list this node (already flagged there)
+    if (lane == 0) {
+      a.q_tok[gi] = 0.f; a.m_int[gi] = 0.f; a.cos_parent[gi] = 0.f; a.n_int[gi] = 0;
+      a.m_conv[gi] = 0.f; a.n_conv[gi] = 0;
+    }
+    return;
+  }
+  if (n_c > MAXW) {
+    if (lane == 0) atomicOr(dev_status, CASCADE_FLAG_WIDTH);
+    n_c = MAXW;
+  }
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
-  // masses over distinct token ids; lane idx owns member idx
-  float mi = 0.f, mc = 0.f;
-  if (lane < n_i) {
-    const int t = tok_i[wave][lane];
-    bool dup = (t == ta) || t < 0 || t >= a.vocab;
-    for (int e = 0; e < lane; ++e) dup |= (tok_i[wave][e] == t);
-    if (!dup) mi = prob_of(Lp, thr, lse, t);
-  }
+  const float* Lp = a.logits + (int64_t)(lo + par) * a.vocab;
+  const float thr = a.row_thr[lo + par], lse = a.row_lse[lo + par];
+  float mc = 0.f;
   if (lane < n_c) {
     const int t = tok_c[wave][lane];
     bool dup = (t == ta) || t < 0 || t >= a.vocab;
@@ -140,239 +264,10 @@ __global__ __launch_bounds__(256) void accept_kernel(accept_args a, int* dev_sta
     for (int e = 0; e < lane; ++e) dup |= (tok_c[wave][e] == t);
     if (!dup) mc = prob_of(Lp, thr, lse, t);
   }
-  mi = wave_sum(mi);
   mc = wave_sum(mc);
   if (lane == 0) {
-    a.q_tok[gi] = tok_ok ? prob_of(Lp, thr, lse, ta) : 0.f;
-    a.m_int[gi] = mi;
     a.m_conv[gi] = mc;
-    a.cos_parent[gi] = cpar;
-    a.n_int[gi] = n_i;
     a.n_conv[gi] = n_c;
-  }
-}
-
-// ------------------------------------------------------------------------------- select_path
-struct TryResult {
-  bool pass;
-  float tvd;
-};
-__device__ __forceinline__ TryResult try_node(const select_args& a, int64_t gi, float tvd) {
-  float q = a.q_tok[gi];
-  if (a.n_int[gi] > 0) {
-    const float m = a.m_int[gi];
-    if (tvd + m <= a.eps_tvd) { q += m; tvd += m; }
-  }
-  if (a.n_conv[gi] > 0) {
-    const float m = a.m_conv[gi];
-    if (tvd + m <= a.eps_tvd) { q += m; tvd += m; }
-  }
-  const float px = a.draft_prob ? a.draft_prob[gi] : 1.f;
-  TryResult r;
-  r.pass = a.u[gi] * px < q;
-  r.tvd = tvd;
-  return r;
-}
-
-constexpr int SEL_THREADS = 256;
-
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int* dev_status) {
-  __shared__ int s_path[CASCADE_MAX_DEPTH];
-  __shared__ int s_best[CASCADE_MAX_DEPTH];
-  __shared__ int s_tried[CASCADE_MAX_WIDTH];
-  __shared__ unsigned char s_haschild[CASCADE_MAX_TREE];
-  __shared__ int s_len, s_cur, s_ntried;
-  __shared__ float s_tvd;
-  __shared__ float s_seg[SEL_THREADS];
-  __shared__ float s_total;
-  __shared__ int s_pick;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b = blockIdx.x;
-  const int lo = a.node_off[b], Tn = min(a.node_off[b + 1] - lo, CASCADE_MAX_TREE);
-  const int maxd = min(a.max_depth, CASCADE_MAX_DEPTH);
-
-  if (a.mode == CASCADE_WALK_LONGEST) {
-    for (int i = tid; i < Tn; i += SEL_THREADS) s_haschild[i] = 0;
-    __syncthreads();
-    for (int i = tid; i < Tn; i += SEL_THREADS) {
-      const int pi = a.parent[lo + i];
-      if (i > 0 && pi >= 0 && pi < i) s_haschild[pi] = 1;
-    }
-    __syncthreads();
-  }
-
-  if (wave == 0) {
-    int cur = 0, len = 0, ntried = 0;
-    float tvd = 0.f;
-    if (a.mode == CASCADE_WALK_SEQUENTIAL) {
-      bool going = true;
-      while (going) {
-        int accepted = -1;
-        ntried = 0;
-        bool any_child = false;
-        for (int base = 0; base < Tn && accepted < 0; base += 64) {
-          const int j = base + lane;
-          unsigned long long kids = __ballot(j > cur && j < Tn && a.parent[lo + j] == cur);
-          while (kids) {
-            const int c = base + __ffsll((long long)kids) - 1;
-            kids &= kids - 1;
-            any_child = true;
-            const TryResult r = try_node(a, lo + c, tvd);
-            tvd = r.tvd;
-            if (r.pass) { accepted = c; break; }
-            if (ntried < CASCADE_MAX_WIDTH) { if (lane == 0) s_tried[ntried] = a.token[lo + c]; ++ntried; }
-            else if (lane == 0) atomicOr(dev_status, CASCADE_FLAG_WIDTH);
-          }
-        }
-        (void)any_child;
-        if (accepted < 0) break;
-        if (len >= maxd) { if (lane == 0) atomicOr(dev_status, CASCADE_FLAG_DEPTH); break; }
-        if (lane == 0) s_path[len] = accepted;
-        ++len;
-        cur = accepted;
-      }
-    } else {
-      int best_len = -1, best_cur = 0, best_ntried = 0, best_tried_tok = -1;
-      float best_tvd = 0.f;
-      for (int leaf = 0; leaf < Tn; ++leaf) {
-        if (s_haschild[leaf]) continue;
-        // chain root -> leaf, climbed into s_path backwards (uniform across the wave)
-        int depth = 0;
-        for (int x = leaf; x > 0 && depth <= CASCADE_MAX_TREE; ) {
-          const int px = a.parent[lo + x];
-          ++depth;
-          if (px < 0 || px >= x) break;
-          x = px;
-        }
-        if (depth > maxd) { if (lane == 0) atomicOr(dev_status, CASCADE_FLAG_DEPTH); continue; }
-        if (lane == 0) {
-          int x = leaf;
-          for (int d = depth - 1; d >= 0; --d) { s_path[d] = x; x = a.parent[lo + x]; }
-        }
-        __builtin_amdgcn_wave_barrier();
-        __threadfence_block();
-        float t = 0.f;
-        int l = 0, c_cur = 0, nt = 0, tt = -1;
-        for (int d = 0; d < depth; ++d) {
-          const int c = s_path[d];
-          const TryResult r = try_node(a, lo + c, t);
-          t = r.tvd;
-          if (!r.pass) { nt = 1; tt = a.token[lo + c]; break; }
-          ++l;
-          c_cur = c;
-        }
-        if (l > best_len) {
-          best_len = l; best_cur = c_cur; best_ntried = nt; best_tried_tok = tt; best_tvd = t;
-          if (lane == 0) for (int d = 0; d < l; ++d) s_best[d] = s_path[d];
-        }
-        __builtin_amdgcn_wave_barrier();
-      }
-      if (best_len < 0) best_len = 0;
-      len = best_len; cur = best_cur; ntried = best_ntried; tvd = best_tvd;
-      if (lane == 0) {
-        for (int d = 0; d < len; ++d) s_path[d] = s_best[d];
-        if (ntried) s_tried[0] = best_tried_tok;
-      }
-    }
-    if (lane == 0) { s_len = len; s_cur = cur; s_ntried = ntried; s_tvd = tvd; }
-  }
-  __syncthreads();
-
-  // correction / bonus token from the terminal node's distribution
-  const int len = s_len, cur = s_cur, ntried = s_ntried;
-  const int V = a.vocab;
-  const float* Lr = a.logits + (int64_t)(lo + cur) * V;
-  const float thr = a.row_thr[lo + cur], lse = a.row_lse[lo + cur];
-  const int seg = (V + SEL_THREADS - 1) / SEL_THREADS;
-  const int v_lo = tid * seg, v_hi = min(V, v_lo + seg);
-  bool use_ban = true;
-  for (int attempt = 0; attempt < 2; ++attempt) {
-    float ssum = 0.f;
-    for (int v = v_lo; v < v_hi; ++v) {
-      const float gv = Lr[v];
-      if (gv >= thr) {
-        bool banned = false;
-        if (use_ban) for (int e = 0; e < ntried; ++e) banned |= (s_tried[e] == v);
-        if (!banned) ssum += __expf(gv - lse);
-      }
-    }
-    s_seg[tid] = ssum;
-    __syncthreads();
-    if (tid == 0) {
-      float tot = 0.f;
-      for (int i = 0; i < SEL_THREADS; ++i) tot += s_seg[i];
-      s_total = tot;
-      s_pick = -1;
-      if (tot > 0.f) {
-        const float target = a.u_bonus[b] * tot;
-        float run = 0.f;
-        int pick = -1;
-        for (int i = 0; i < SEL_THREADS; ++i) {
-          if (run + s_seg[i] > target) { pick = i; break; }
-          run += s_seg[i];
-        }
-        s_pick = pick;            // -1: never exceeded (rounding) -> last kept entry
-        s_seg[0] = run;           // mass before the picked segment (s_seg[0] no longer needed: see below)
-      }
-    }
-    __syncthreads();
-    if (s_total > 0.f) break;
-    use_ban = false;              // everything was removed: fall back to the unfiltered row
-    __syncthreads();
-  }
-  const float total = s_total;
-  const int pick = s_pick;
-  // NOTE: s_seg[0] now holds the running mass before segment `pick` (written by thread 0 after
-  // every read of s_seg in the scan above).
-  if (pick >= 0 && tid == pick) {
-    const float target = a.u_bonus[b] * total;
-    float run = s_seg[0];
-    int x = -1;
-    for (int v = v_lo; v < v_hi; ++v) {
-      const float gv = Lr[v];
-      if (gv >= thr) {
-        bool banned = false;
-        if (use_ban) for (int e = 0; e < ntried; ++e) banned |= (s_tried[e] == v);
-        if (!banned) {
-          run += __expf(gv - lse);
-          x = v;
-          if (run > target) break;
-        }
-      }
-    }
-    a.emitted[(int64_t)b * (a.max_depth + 1) + len] = x;
-  }
-  if (pick < 0) {
-    // fall-back: last kept, not banned entry of the row (block-wide max of candidate indices)
-    int last = -1;
-    for (int v = v_lo; v < v_hi; ++v) {
-      const float gv = Lr[v];
-      if (gv >= thr) {
-        bool banned = false;
-        if (use_ban) for (int e = 0; e < ntried; ++e) banned |= (s_tried[e] == v);
-        if (!banned) last = v;
-      }
-    }
-    __syncthreads();
-    s_seg[tid] = (float)last;
-    __syncthreads();
-    if (tid == 0) {
-      float m = -1.f;
-      for (int i = 0; i < SEL_THREADS; ++i) m = fmaxf(m, s_seg[i]);
-      a.emitted[(int64_t)b * (a.max_depth + 1) + len] = (int)m;
-    }
-  }
-  // the rest of the outputs
-  for (int d = tid; d < a.max_depth; d += SEL_THREADS)
-    a.path_nodes[(int64_t)b * a.max_depth + d] = d < len ? s_path[d] : -1;
-  for (int d = tid; d <= a.max_depth; d += SEL_THREADS) {
-    if (d < len) a.emitted[(int64_t)b * (a.max_depth + 1) + d] = a.token[lo + s_path[d]];
-    else if (d > len) a.emitted[(int64_t)b * (a.max_depth + 1) + d] = -1;
-  }
-  if (tid == 0) {
-    a.accept_len[b] = len;
-    a.terminal[b] = cur;
-    a.tvd_used[b] = s_tvd;
   }
 }
 
@@ -381,17 +276,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
 hipError_t launch_accept(cascade_ctx* ctx, const accept_args* a) {
   hipStream_t stream = ctx->stream;
   int* dev_status = ctx->dev_status;
-  dim3 grid((ctx->lim.max_nodes_per_tree + 3) / 4, a->n_prompts);
+  unsigned long long* imask = (unsigned long long*)ctx->imask_ws;
   KernelTimer t(ctx, CASCADE_K_ACCEPT);
-  if (a->h_dtype == CASCADE_BF16) hipLaunchKernelGGL(accept_kernel<uint16_t>, grid, dim3(256), 0, stream, *a, dev_status);
-  else hipLaunchKernelGGL(accept_kernel<float>, grid, dim3(256), 0, stream, *a, dev_status);
-  return hipGetLastError();
-}
-
-hipError_t launch_select(cascade_ctx* ctx, const select_args* a) {
-  hipStream_t stream = ctx->stream;
-  int* dev_status = ctx->dev_status;
-  KernelTimer t(ctx, CASCADE_K_SELECT);
-  hipLaunchKernelGGL(select_kernel, dim3(a->n_prompts), dim3(SEL_THREADS), 0, stream, *a, dev_status);
+  dim3 g1(ctx->lim.max_nodes_per_tree, a->n_prompts);
+  if (a->h_dtype == CASCADE_BF16) hipLaunchKernelGGL(accept_gram_kernel<uint16_t>, g1, dim3(256), 0, stream, *a, imask, dev_status);
+  else hipLaunchKernelGGL(accept_gram_kernel<float>, g1, dim3(256), 0, stream, *a, imask, dev_status);
+  dim3 g2((ctx->lim.max_nodes_per_tree + 3) / 4, a->n_prompts);
+  hipLaunchKernelGGL(accept_conv_kernel, g2, dim3(256), 0, stream, *a, imask, dev_status);
   return hipGetLastError();
 }

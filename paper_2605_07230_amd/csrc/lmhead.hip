@@ -174,8 +174,10 @@ __global__ __launch_bounds__(256) void pack32_kernel(const uint16_t* __restrict_
   dst[((int64_t)rb * (K / 16) + ks) * 64 + lane] = v;
 }
 
-template <bool CFG>
+// NSTEPS > 0: k16 steps per wave known at compile time (K = 64 * NSTEPS), deep fully unrolled pipeline.
+template <bool CFG, int NSTEPS>
 __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
+  constexpr bool DEEP = NSTEPS > 0;
   constexpr int NA = CFG ? 4 : 2;
   extern __shared__ float red[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -206,34 +208,77 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int n_slices = (K / 128 - wave + 3) / 4;
-  const int n_groups = 2 * n_slices;
-  auto ks_of = [&](int gi) { return (wave + 4 * (gi >> 1)) * 8 + 4 * (gi & 1); };   // first k16 step of the group
-  auto load_group = [&](Group<CFG>& G, int ks) {
+  const int n_slices = (K / 128 - wave + 3) / 4;   // 128-wide slices wave, wave+4, ... of the hidden dimension
+  if constexpr (DEEP) {
+    // Deep software pipeline, one k16 step at a time.
+    // W streams from HBM: requested WD = 16 steps ahead (32 KiB in flight per wave).  H comes from
+    // L2: requested HD = 8 steps ahead.  Registers: 32 + 32 operand fragments and 8 accumulators.
+    // After a step's MFMAs its own ring slots are refilled, H first, so that waiting for the H
+    // fragment of a later step never waits for younger W requests.
+    constexpr int HD = 8, WD = 16;
+    static_assert(!DEEP || (NSTEPS % 8 == 0 && NSTEPS >= WD), "whole 128-wide slices per wave");
+    auto ks_of_step = [&](int t) { return (wave + 4 * (t >> 3)) * 8 + (t & 7); };
+    Frag8 hr[HD][NA];
+    Frag8 wr[WD][2];
+    auto load_h = [&](int slot, int t) {
+      const int64_t o = (int64_t)ks_of_step(t) * 64;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
+      for (int i = 0; i < NA; ++i) hr[slot][i].u = ap[i][o];
+    };
+    auto load_w = [&](int slot, int t) {
+      const int64_t o = (int64_t)ks_of_step(t) * 64;
 #pragma unroll
-      for (int i = 0; i < NA; ++i) G.a[s][i].u = ap[i][(int64_t)(ks + s) * 64];
+      for (int j = 0; j < 2; ++j) wr[slot][j].u = bp[j][o];
+    };
+    // prologue in the same request order as the steady state (..., H(t+8), W(t+16), ...)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) G.b[s][j].u = bp[j][(int64_t)(ks + s) * 64];
+    for (int t = 0; t < WD - HD; ++t) load_w(t, t);
+#pragma unroll
+    for (int t = 0; t < HD; ++t) {
+      load_h(t, t);
+      load_w(WD - HD + t, WD - HD + t);
     }
-  };
-  auto compute_group = [&](const Group<CFG>& G) {
+    // fully unrolled: the whole schedule is straight-line code with exact outstanding-load counts
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
+    for (int t = 0; t < NSTEPS; ++t) {
 #pragma unroll
       for (int i = 0; i < NA; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(G.a[s][i].v, G.b[s][j].v, acc[i][j], 0, 0, 0);
-  };
-  Group<CFG> g0, g1;
-  if (n_groups > 0) load_group(g0, ks_of(0));
-  for (int gi = 0; gi < n_groups; gi += 2) {
-    load_group(g1, ks_of(gi + 1));
-    compute_group(g0);
-    if (gi + 2 < n_groups) load_group(g0, ks_of(gi + 2));
-    compute_group(g1);
+        for (int jj = 0; jj < 2; ++jj)
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hr[t % HD][i].v, wr[t % WD][jj].v, acc[i][jj], 0, 0, 0);
+      if (t + HD < NSTEPS) load_h(t % HD, t + HD);
+      if (t + WD < NSTEPS) load_w(t % WD, t + WD);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+    const int n_groups = 2 * n_slices;
+    auto ks_of = [&](int gi) { return (wave + 4 * (gi >> 1)) * 8 + 4 * (gi & 1); };   // first k16 step of the group
+    auto load_group = [&](Group<CFG>& G, int ks) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) G.a[s][i].u = ap[i][(int64_t)(ks + s) * 64];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) G.b[s][j].u = bp[j][(int64_t)(ks + s) * 64];
+      }
+    };
+    auto compute_group = [&](const Group<CFG>& G) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(G.a[s][i].v, G.b[s][j].v, acc[i][j], 0, 0, 0);
+    };
+    Group<CFG> g0, g1;
+    if (n_groups > 0) load_group(g0, ks_of(0));
+    for (int gi = 0; gi < n_groups; gi += 2) {
+      load_group(g1, ks_of(gi + 1));
+      compute_group(g0);
+      if (gi + 2 < n_groups) load_group(g0, ks_of(gi + 2));
+      compute_group(g1);
+    }
   }
 
   constexpr int NACC = NA * 2;
@@ -261,8 +306,8 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
 
 // ------------------------------------------------------------------------------------ row stats
 // One workgroup of 1024 threads per row; the row lives in registers (VPT values per thread).
-// row_max, exact k-th largest (bitwise radix select on order-preserving integer keys), and
-// log-sum-exp over the kept entries.
+// row_max, exact k-th largest (radix select on order-preserving integer keys), and log-sum-exp
+// over the kept entries.
 __device__ __forceinline__ uint32_t f32_key(float f) {
   uint32_t u = __float_as_uint(f);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
@@ -271,13 +316,35 @@ __device__ __forceinline__ float key_f32(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
+__device__ __forceinline__ int wave_scan_incl_i(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(v, o, WAVE);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// Exact k-th largest in three stages: (1) a 4096-bin histogram of the top 12 key bits (LDS integer
+// atomics) and a scan from the top locate the bin holding the k-th largest; (2) the keys of that
+// bin are compacted into LDS; (3) one wave resolves the remaining 20 bits bit by bit over the few
+// candidates.  If the bin holds more than CAND_MAX keys (degenerate rows, e.g. all equal) the 20
+// bits are resolved by the whole workgroup over its registers instead.
+constexpr int HBINS = 4096, CAND_MAX = 4096;
+
 template <int VPT>
 __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
   __shared__ float fred[16];
   __shared__ int ired[2][16];
+  __shared__ int hist[HBINS];
+  __shared__ uint32_t cand[CAND_MAX];
+  __shared__ int s_wsum[16];
+  __shared__ int s_bin, s_above, s_cnt;
+  __shared__ uint32_t s_thr;
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int V = p.vocab;
   const float* g = p.logits + (int64_t)row * V;
+  const bool topk = p.top_k > 0 && p.top_k < V;
   // the row is held as order-preserving integer keys; values are recovered from them when needed
   uint32_t key[VPT];
   float mx = -INFINITY;
@@ -288,6 +355,11 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
     key[i] = f32_key(xv);
     mx = fmaxf(mx, xv);
   }
+  if (topk) {
+#pragma unroll
+    for (int i = 0; i < HBINS / 1024; ++i) hist[tid + 1024 * i] = 0;
+    if (tid == 0) s_cnt = 0;
+  }
   mx = wave_max(mx);
   if (lane == 0) fred[wave] = mx;
   __syncthreads();
@@ -295,22 +367,61 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
 #pragma unroll
   for (int w = 1; w < 16; ++w) mx = fmaxf(mx, fred[w]);
 
-  uint32_t thr_key = 0;            // key of -inf or below: keeps everything
+  uint32_t thr_key = 0;            // keeps everything
   float thr = -INFINITY;
-  if (p.top_k > 0 && p.top_k < V) {
-    uint32_t prefix = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t cand = prefix | (1u << bit);
-      int cnt = 0;
+  if (topk) {
 #pragma unroll
-      for (int i = 0; i < VPT; ++i) cnt += __popcll(__ballot(key[i] >= cand));
-      const int buf = bit & 1;
-      if (lane == 0) ired[buf][wave] = cnt;
+    for (int i = 0; i < VPT; ++i)
+      if (tid + 1024 * i < V) atomicAdd(&hist[key[i] >> 20], 1);
+    __syncthreads();
+    // thread t owns the bins 4095-4t .. 4095-4t-3 (counting down from the largest keys)
+    int hb[4], loc = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { hb[i] = hist[HBINS - 1 - (4 * tid + i)]; loc += hb[i]; }
+    const int incl = wave_scan_incl_i(loc, lane);
+    if (lane == 63) s_wsum[wave] = incl;
+    __syncthreads();
+    int before = incl - loc;
+    for (int w = 0; w < wave; ++w) before += s_wsum[w];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (before < p.top_k && before + hb[i] >= p.top_k) { s_bin = HBINS - 1 - (4 * tid + i); s_above = before; }
+      before += hb[i];
+    }
+    __syncthreads();
+    const int bin = s_bin, k2 = p.top_k - s_above, n2 = hist[bin];
+    uint32_t prefix = (uint32_t)bin << 20;
+    if (n2 <= CAND_MAX) {
+#pragma unroll
+      for (int i = 0; i < VPT; ++i)
+        if (tid + 1024 * i < V && (int)(key[i] >> 20) == bin) cand[atomicAdd(&s_cnt, 1)] = key[i];
       __syncthreads();
-      int tot = 0;
+      if (wave == 0) {
+        for (int bit = 19; bit >= 0; --bit) {
+          const uint32_t c = prefix | (1u << bit);
+          int cnt = 0;
+          for (int e = lane; e < n2; e += 64) cnt += cand[e] >= c;
+          cnt = wave_sum_i(cnt);
+          if (cnt >= k2) prefix = c;
+        }
+        if (lane == 0) s_thr = prefix;
+      }
+      __syncthreads();
+      prefix = s_thr;
+    } else {
+      for (int bit = 19; bit >= 0; --bit) {
+        const uint32_t c = prefix | (1u << bit);
+        int cnt = 0;
 #pragma unroll
-      for (int w = 0; w < 16; ++w) tot += ired[buf][w];
-      if (tot >= p.top_k) prefix = cand;
+        for (int i = 0; i < VPT; ++i) cnt += __popcll(__ballot(tid + 1024 * i < V && key[i] >= c));
+        const int buf = bit & 1;
+        if (lane == 0) ired[buf][wave] = cnt;
+        __syncthreads();
+        int tot = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) tot += ired[buf][w];
+        if (tot >= p.top_k) prefix = c;
+      }
     }
     thr_key = prefix;
     thr = key_f32(prefix);
@@ -367,10 +478,10 @@ hipError_t launch_lmhead_f32(cascade_ctx* ctx, const lmhead_args* a) {
   return hipGetLastError();
 }
 
-template <bool CFG, bool PACKED>
+template <bool CFG, int KIND>   // KIND 0: row-major W, 1: packed, 2: packed with the deep pipeline
 hipError_t launch_bf16_gemm(cascade_ctx* ctx, const LmParams& p, int grid) {
   const size_t smem = (size_t)4 * (CFG ? 8 : 4) * 16 * 64 * sizeof(float);
-  auto kern = PACKED ? lmhead_bf16_packed_kernel<CFG> : lmhead_bf16_kernel<CFG>;
+  auto kern = KIND == 2 ? lmhead_bf16_packed_kernel<CFG, 64> : (KIND == 1 ? lmhead_bf16_packed_kernel<CFG, 0> : lmhead_bf16_kernel<CFG>);
   static bool attr_done = false;   // one flag per template instance
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -400,9 +511,10 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
     if (e != hipSuccess) return e;
     p.hp_cond = hc;
     p.hp_uncond = hu;
-    return cfg ? launch_bf16_gemm<true, true>(ctx, p, grid) : launch_bf16_gemm<false, true>(ctx, p, grid);
+    if (a->hidden == 4096) return cfg ? launch_bf16_gemm<true, 2>(ctx, p, grid) : launch_bf16_gemm<false, 2>(ctx, p, grid);
+    return cfg ? launch_bf16_gemm<true, 1>(ctx, p, grid) : launch_bf16_gemm<false, 1>(ctx, p, grid);
   }
-  return cfg ? launch_bf16_gemm<true, false>(ctx, p, grid) : launch_bf16_gemm<false, false>(ctx, p, grid);
+  return cfg ? launch_bf16_gemm<true, 0>(ctx, p, grid) : launch_bf16_gemm<false, 0>(ctx, p, grid);
 }
 
 hipError_t launch_pack_w(cascade_ctx* ctx, const void* w, int vocab, int hidden, void* w_packed) {

@@ -153,6 +153,18 @@ def test_packed_and_row_major_weights_agree_bitwise_on_statistics():
     assert torch.equal(a.emitted, b.emitted)
 
 
+def test_rows_with_all_equal_logits_take_the_wide_bin_path():
+    # zero hidden states give a row of identical logits: every entry ties with the k-th largest and is kept
+    inp = _small_bf16(7, n_prompts=1, prefix_lens=[8, 8], trees=[wl.grow_tree(np.random.default_rng(7), 12, 3, 4)],
+                      hidden=128, vocab=8192, top_k=100, align=0.0)
+    inp.h_cond[3] = 0.0
+    inp.h_uncond[3] = 0.0
+    ds = pu.run_gpu_step(inp)
+    pu.check_lmhead(inp, ds)
+    assert float(ds.row_thr[3]) == 0.0 and abs(float(ds.row_lse[3]) - np.log(8192.0)) < 1e-5
+    pu.check_accept_and_path(inp, ds, require_margin=False)
+
+
 def test_f32_ragged_batch():
     rng = np.random.default_rng(4)
     inp = _small_bf16(4, dtype="f32", head_dim=32, hidden=96, vocab=300, top_k=20,
