@@ -129,9 +129,15 @@ struct AttnSmem {
   unsigned long long anc[256];
 };
 
+// two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  return (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
+  const bf16x2_t v = __builtin_convertvector(f32x2_t{a, b}, bf16x2_t);
+  return *(const uint32_t*)&v;
 }
+// 2^x for x <= 0 or -inf (v_exp_f32; no range handling needed here)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 union Frag8 {
   bf16x8 v;
@@ -316,13 +322,13 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
       mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
       const float m_new = fmaxf(m_run[n], mx);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = exp2f(m_run[n] - m_use);   // -inf - finite = -inf -> 0
+      const float alpha = fast_exp2(m_run[n] - m_use);   // -inf - finite = -inf -> 0
       float ls = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          const float e = exp2f(st[n][kt][c] - m_use);
+          const float e = fast_exp2(st[n][kt][c] - m_use);
           st[n][kt][c] = e;
           ls += e;
         }
@@ -382,6 +388,295 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
         *(uint2*)(o + 16 * db + 4 * g) = w;
       }
       if (g == 0 && p.lse) p.lse[out_row[n]] = m_run[n] * LN2 + logf(l);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------- bf16, small trees
+// Workgroup = (row, kv head, 64 query rows, kv split), NKG key groups x 4 query blocks of waves.
+// In every round the key groups take NKG consecutive 64-key tiles; the four waves of a
+// group copy their tile into the group's LDS buffer (each a quarter of it), then each wave runs
+// its own 16 query rows against it.  The next round's tile is requested from memory before the
+// current one is consumed.  K and V are both stored row-major with plain 16-byte stores; the V^T
+// operand of the second MFMA is read with the transposing LDS load (ds_read_b64_tr_b16): inside
+// each group of 16 lanes, lane i passes the address of 4 consecutive d of key (i / 4), and lane L
+// receives the 4 keys at d + L.  The key groups' (m, l, O) are merged through LDS at the
+// end, so a drafted tree against a short prefix needs neither workspace traffic nor a second kernel.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+struct KsplitGroupSmem {
+  static constexpr int KP = D + 8;      // K row pitch (elements)
+  static constexpr int VP = D + 16;     // V row pitch (elements): 4 consecutive keys fall on distinct bank groups
+  uint16_t k[KT * KP];
+  uint16_t v[KT * VP];
+};
+
+// NKG = key groups (the workgroup has NKG * 4 waves)
+template <int D, int NKG, bool SPLIT>
+__global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams p) {
+  constexpr int NT = NKG * 256;
+  using GS = KsplitGroupSmem<D>;
+  extern __shared__ __align__(16) char smem_raw[];
+  constexpr int KS = D / 32, DB = D / 16, DC = D / 8;
+  constexpr int OP = D + 4;            // merge buffer row pitch (floats)
+  constexpr int NPC = KT * DC / 256;   // 16-byte pieces of K (and of V) each lane copies per tile
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kg = wave >> 2, qb = wave & 3;     // key group, query block
+  const int gl = tid & 255;                    // lane index inside the key group
+  const int l16 = lane & 15, g = lane >> 4;
+  GS* gs = (GS*)smem_raw + kg;
+  int* s_parent = (int*)(smem_raw + NKG * sizeof(GS));                                         // [CASCADE_MAX_TREE]
+  unsigned long long* s_anc = (unsigned long long*)(s_parent + CASCADE_MAX_TREE) + 64 * kg;   // [NKG][64]
+  const int s = blockIdx.z, kvh = blockIdx.y;
+  const int split = blockIdx.x % p.n_split, sb = blockIdx.x / p.n_split;
+  const int lo = p.node_off[s];
+  const int T = p.node_off[s + 1] - lo;
+  const int P = p.prefix_len[s];
+  const int G = p.group;
+  const int M = T * G;
+  const int row0 = sb * 64;
+  if (row0 >= M || T > CASCADE_MAX_TREE) return;
+  const int n_pt = (P + KT - 1) / KT, n_tt = (T + KT - 1) / KT, nt = n_pt + n_tt;
+  const int per = (nt + p.n_split - 1) / p.n_split;
+  const int t_begin = split * per, t_end = min(nt, t_begin + per);
+  const int n_rounds = (max(t_end - t_begin, 0) + NKG - 1) / NKG;
+
+  const uint16_t* kc = (const uint16_t*)p.k_cache + s * p.sr + kvh * p.sh;
+  const uint16_t* vc = (const uint16_t*)p.v_cache + s * p.sr + kvh * p.sh;
+  const uint16_t* ktr = (const uint16_t*)p.k_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D;
+  const uint16_t* vtr = (const uint16_t*)p.v_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D;
+  const int64_t tree_pitch = (int64_t)p.n_kv_heads * D;
+
+  // a quarter of the group's tile per wave: pieces gl, gl + 256, ... (piece c = key c / DC, 8 d at c % DC)
+  uint4 kr[NPC], vr[NPC];
+  auto request_tile = [&](int t) {
+    const bool tree_tile = t >= n_pt;
+    const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
+    const int klimit = tree_tile ? T : P;
+    const uint16_t* ksrc = tree_tile ? ktr : kc;
+    const uint16_t* vsrc = tree_tile ? vtr : vc;
+    const int64_t pitch = tree_tile ? tree_pitch : p.sp;
+#pragma unroll
+    for (int it = 0; it < NPC; ++it) {
+      const int c = gl + 256 * it, key = c / DC, dc = c % DC;
+      kr[it] = make_uint4(0, 0, 0, 0);
+      vr[it] = make_uint4(0, 0, 0, 0);
+      if (t < t_end && kbase + key < klimit) {
+        kr[it] = *(const uint4*)(ksrc + (int64_t)(kbase + key) * pitch + 8 * dc);
+        vr[it] = *(const uint4*)(vsrc + (int64_t)(kbase + key) * pitch + 8 * dc);
+      }
+    }
+  };
+  request_tile(t_begin + kg);   // first round's tile: in flight while queries and parents are fetched
+
+  if (t_end > n_pt) {
+    for (int i = tid; i < T; i += NT) {
+      int pi = p.parent[lo + i];
+      if (pi >= i || pi < -1 || (i == 0 && pi != -1) || (i > 0 && pi < 0)) {
+        atomicOr(p.dev_status, CASCADE_FLAG_PARENT);
+        pi = (i == 0) ? -1 : 0;
+      }
+      s_parent[i] = pi;
+    }
+  }
+
+  // this wave's 16 query rows (B operand of S^T): lane = (query l16, d group g)
+  Frag8 qf[KS];
+  const int qr = row0 + 16 * qb + l16;
+  const bool q_ok = qr < M;
+  {
+    const int i = q_ok ? qr % T : 0, hg = q_ok ? qr / T : 0;
+    const uint16_t* qp = (const uint16_t*)p.q + ((int64_t)(lo + i) * p.n_heads + kvh * G + hg) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (q_ok) qf[ks].u = *(const uint4*)(qp + 32 * ks);
+      else qf[ks].u = make_uint4(0, 0, 0, 0);
+    }
+  }
+  f32x4 ot[DB];
+  float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+  for (int db = 0; db < DB; ++db) ot[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int r = 0; r < n_rounds; ++r) {
+    const int t = t_begin + NKG * r + kg;
+    const bool active = t < t_end;
+    const bool tree_tile = t >= n_pt;
+    const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
+    const int klimit = tree_tile ? T : P;
+    __syncthreads();   // previous round's tiles are consumed (and, in round 0, the parent array is complete)
+#pragma unroll
+    for (int it = 0; it < NPC; ++it) {
+      const int c = gl + 256 * it, key = c / DC, dc = c % DC;
+      *(uint4*)(&gs->k[key * GS::KP + 8 * dc]) = kr[it];
+      *(uint4*)(&gs->v[key * GS::VP + 8 * dc]) = vr[it];
+    }
+    if (active && tree_tile && qb == 0) {
+      // ancestor-or-self bits of this tile's 64 tree keys for query row (row0 + lane)
+      const int rr = row0 + lane;
+      unsigned long long wbits = 0ull;
+      if (rr < M) {
+        int a = rr % T, guard = 0;
+        while (a >= 0 && guard++ <= CASCADE_MAX_TREE) {
+          const int rel = a - kbase;
+          if (rel < 0) break;
+          if (rel < 64) wbits |= 1ull << rel;
+          a = s_parent[a];
+        }
+      }
+      s_anc[lane] = wbits;
+    }
+    if (r + 1 < n_rounds) request_tile(t + NKG);   // next round streams in while this one is consumed
+    __syncthreads();
+    if (!active) continue;
+
+    // S^T = K Q^T : st[kt] holds keys 16*kt + 4*g + c for query l16
+    f32x4 st[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        Frag8 kf;
+        kf.u = *(const uint4*)(&gs->k[(16 * kt + l16) * GS::KP + 32 * ks + 8 * g]);
+        st[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[ks].v, st[kt], 0, 0, 0);
+      }
+    }
+    unsigned long long valid;
+    if (tree_tile) {
+      valid = s_anc[16 * qb + l16];
+    } else {
+      const int rem = klimit - kbase;
+      valid = rem >= 64 ? ~0ull : ((1ull << rem) - 1ull);
+    }
+    if (!q_ok) valid = 0ull;
+    float mx = -INFINITY;
+    if (__ballot(valid != ~0ull) == 0ull) {
+      // every key of the tile is visible to every query of the block: no masking
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          st[kt][c] *= p.scale_log2e;
+          mx = fmaxf(mx, st[kt][c]);
+        }
+    } else {
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) {
+        const uint32_t nib = (uint32_t)(valid >> (16 * kt + 4 * g));   // this lane's 4 keys of sub-tile kt
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float z = ((nib >> c) & 1u) ? st[kt][c] * p.scale_log2e : -INFINITY;
+          st[kt][c] = z;
+          mx = fmaxf(mx, z);
+        }
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2(m_run - m_use);
+    float ls = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float e = fast_exp2(st[kt][c] - m_use);
+        st[kt][c] = e;
+        ls += e;
+      }
+    l_run = l_run * alpha + ls;
+    m_run = m_new;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) ot[db] *= alpha;
+    Frag8 pf[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      pf[j].u.x = pack_bf16x2(st[2 * j][0], st[2 * j][1]);
+      pf[j].u.y = pack_bf16x2(st[2 * j][2], st[2 * j][3]);
+      pf[j].u.z = pack_bf16x2(st[2 * j + 1][0], st[2 * j + 1][1]);
+      pf[j].u.w = pack_bf16x2(st[2 * j + 1][2], st[2 * j + 1][3]);
+    }
+    // O^T += V^T P^T.  Operand slots of lane (l16, g): keys 32j + 4g + {0..3} and 32j + 16 + 4g + {0..3}
+    // at d = 16 db + l16, fetched by two transposing loads from the row-major V tile.
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const uint16_t* vp = &gs->v[(32 * j + 4 * g + (l16 >> 2)) * GS::VP + 16 * db + 4 * (l16 & 3)];
+        union { Frag8 f; s16x4 h[2]; } vf;
+        vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp));
+        vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp + 16 * GS::VP));
+        ot[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.f.v, pf[j].v, ot[db], 0, 0, 0);
+      }
+    }
+  }
+
+  // merge the four key groups through LDS (the tile buffers are reused)
+  l_run += __shfl_xor(l_run, 16, WAVE);
+  l_run += __shfl_xor(l_run, 32, WAVE);
+  __syncthreads();
+  float* mo = (float*)smem_raw;                 // [NKG][64 rows][OP]
+  float* mml = mo + NKG * 64 * OP;              // [NKG][64 rows][2]
+  {
+    float* orow = mo + ((kg * 64) + 16 * qb + l16) * OP;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) *(f32x4*)(orow + 16 * db + 4 * g) = ot[db];
+    if (g == 0) {
+      mml[((kg * 64) + 16 * qb + l16) * 2] = m_run;
+      mml[((kg * 64) + 16 * qb + l16) * 2 + 1] = l_run;
+    }
+  }
+  __syncthreads();
+  {
+    constexpr int TPR = NT / 64;                 // threads per output row
+    constexpr int DQ = D / TPR;                  // d range of one thread
+    const int row = tid / TPR, dq = tid % TPR;
+    const int rr = row0 + row;
+    if (rr < M) {
+      float mw[NKG], m = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < NKG; ++w) { mw[w] = mml[(w * 64 + row) * 2]; m = fmaxf(m, mw[w]); }
+      float l = 0.f, o[DQ];
+#pragma unroll
+      for (int d = 0; d < DQ; ++d) o[d] = 0.f;
+#pragma unroll
+      for (int w = 0; w < NKG; ++w) {
+        if (mw[w] == -INFINITY) continue;
+        const float sc = fast_exp2(mw[w] - m);
+        l += sc * mml[(w * 64 + row) * 2 + 1];
+        const float* orow = mo + (w * 64 + row) * OP + DQ * dq;
+#pragma unroll
+        for (int d = 0; d < DQ; d += 4) {
+          const f32x4 v4 = *(const f32x4*)(orow + d);
+          o[d] += sc * v4[0]; o[d + 1] += sc * v4[1]; o[d + 2] += sc * v4[2]; o[d + 3] += sc * v4[3];
+        }
+      }
+      const int i = rr % T, hg = rr / T;
+      const int64_t rowg = (int64_t)(lo + i) * p.n_heads + kvh * G + hg;
+      if (SPLIT) {
+        float* wo = p.ws_o + ((int64_t)split * p.n_rows_total + rowg) * D + DQ * dq;
+#pragma unroll
+        for (int d = 0; d < DQ; d += 4) *(f32x4*)(wo + d) = f32x4{o[d], o[d + 1], o[d + 2], o[d + 3]};
+        if (dq == 0) {
+          float* wm = p.ws_ml + ((int64_t)split * p.n_rows_total + rowg) * 2;
+          wm[0] = m;
+          wm[1] = l;
+        }
+      } else {
+        const float inv = 1.f / l;
+        uint16_t* op = (uint16_t*)p.out + rowg * D + DQ * dq;
+#pragma unroll
+        for (int d = 0; d < DQ; d += 4) {
+          uint2 w2;
+          w2.x = pack_bf16x2(o[d] * inv, o[d + 1] * inv);
+          w2.y = pack_bf16x2(o[d + 2] * inv, o[d + 3] * inv);
+          *(uint2*)(op + d) = w2;
+        }
+        if (dq == 0 && p.lse) p.lse[rowg] = m * LN2 + logf(l);
+      }
     }
   }
 }
@@ -470,17 +765,64 @@ hipError_t launch_tree_attn_f32(cascade_ctx* ctx, const tree_attn_args* a) {
   return hipGetLastError();
 }
 
+template <int D>
+hipError_t launch_ksplit_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
+  // two key groups (8 waves, <= 256 registers each, 2 workgroups per CU) for head_dim 128; four for 64
+  constexpr int NKG = D > 64 ? 2 : 4;
+  hipStream_t st = ctx->stream;
+  const size_t smem = NKG * sizeof(KsplitGroupSmem<D>) + CASCADE_MAX_TREE * sizeof(int) + NKG * 64 * sizeof(unsigned long long);
+  static_assert(NKG * 64 * (D + 4) * 4 + NKG * 64 * 2 * 4 <= NKG * sizeof(KsplitGroupSmem<D>), "merge buffers fit in the tile buffers");
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_ksplit_kernel<D, NKG, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_bf16_ksplit_kernel<D, NKG, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (p.n_split > 1) {
+    {
+      KernelTimer t(ctx, CASCADE_K_ATTN);
+      hipLaunchKernelGGL((attn_bf16_ksplit_kernel<D, NKG, true>), grid, dim3(NKG * 256), smem, st, p);
+    }
+    KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
+    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
+  } else {
+    KernelTimer t(ctx, CASCADE_K_ATTN);
+    hipLaunchKernelGGL((attn_bf16_ksplit_kernel<D, NKG, false>), grid, dim3(NKG * 256), smem, st, p);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a) {
   AttnParams p = make_params(ctx, a);
   const int M = a->max_nodes_per_tree * p.group;   // query rows per (row, kv head)
+  const int n_tiles = (a->max_prefix_len + KT - 1) / KT + (a->max_nodes_per_tree + KT - 1) / KT;
+  const size_t per_split = (size_t)p.n_rows_total * (a->head_dim + 2) * sizeof(float);
+  if (M <= 128) {
+    // small trees: key groups split the tiles inside the workgroup; split across workgroups only when a
+    // workgroup would otherwise walk more than 16 tiles (4 rounds) and the GPU is not yet full
+    p.n_sb = (M + 63) / 64;
+    const long base_wgs = (long)a->n_rows * a->n_kv_heads * p.n_sb;
+    int n_split = (n_tiles + 15) / 16;
+    const int fill = (int)((512 + base_wgs - 1) / base_wgs);
+    if (n_split > fill) n_split = fill;
+    if (n_split > 16) n_split = 16;
+    if (n_split > 1 && per_split * n_split > ctx->attn_ws_bytes) n_split = (int)(ctx->attn_ws_bytes / per_split);
+    if (n_split < 1) n_split = 1;
+    p.n_split = n_split;
+    if (n_split > 1) {
+      p.ws_o = (float*)ctx->attn_ws;
+      p.ws_ml = (float*)(ctx->attn_ws + (size_t)n_split * p.n_rows_total * a->head_dim * sizeof(float));
+    }
+    dim3 grid(n_split * p.n_sb, a->n_kv_heads, a->n_rows);
+    return a->head_dim == 128 ? launch_ksplit_t<128>(ctx, p, grid) : launch_ksplit_t<64>(ctx, p, grid);
+  }
   const int NQ = M <= 64 ? 1 : (M <= 128 ? 2 : 4);
   p.n_sb = (M + 64 * NQ - 1) / (64 * NQ);
-  const int n_tiles = (a->max_prefix_len + KT - 1) / KT + (a->max_nodes_per_tree + KT - 1) / KT;
   const long base_wgs = (long)a->n_rows * a->n_kv_heads * p.n_sb;
   int n_split = (int)((512 + base_wgs - 1) / base_wgs);
   if (n_split > n_tiles) n_split = n_tiles;
   if (n_split > 16) n_split = 16;
-  const size_t per_split = (size_t)p.n_rows_total * (a->head_dim + 2) * sizeof(float);
   if (n_split > 1 && per_split * n_split > ctx->attn_ws_bytes) n_split = (int)(ctx->attn_ws_bytes / per_split);
   if (n_split < 1) n_split = 1;
   p.n_split = n_split;

@@ -70,20 +70,58 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define WAVE 64
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+// Wave-wide scans and reductions on the DPP cross-lane network (no LDS traffic): a Hillis-Steele
+// scan inside each row of 16 lanes (row_shr 1, 2, 4, 8), then the row totals are carried across
+// rows with row_bcast:15 (into rows 1 and 3) and row_bcast:31 (into rows 2 and 3).  Lane 63 ends up
+// holding the total.  Lanes with no source lane receive the operation's identity.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32(float identity, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i32(int identity, int v) {
+  return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
+}
+#define CASCADE_DPP_SCAN(v, OP, ID, FN)          \
+  v = OP(v, FN<0x111, 0xf>(ID, v));              \
+  v = OP(v, FN<0x112, 0xf>(ID, v));              \
+  v = OP(v, FN<0x114, 0xf>(ID, v));              \
+  v = OP(v, FN<0x118, 0xf>(ID, v));              \
+  v = OP(v, FN<0x142, 0xa>(ID, v));              \
+  v = OP(v, FN<0x143, 0xc>(ID, v));
+
+__device__ __forceinline__ float op_add_f(float a, float b) { return a + b; }
+__device__ __forceinline__ int op_add_i(int a, int b) { return a + b; }
+__device__ __forceinline__ int op_min_i(int a, int b) { return min(a, b); }
+__device__ __forceinline__ int op_max_i(int a, int b) { return max(a, b); }
+
+__device__ __forceinline__ float wave_scan_incl_f(float v) {
+  CASCADE_DPP_SCAN(v, op_add_f, 0.f, dpp_f32)
   return v;
+}
+__device__ __forceinline__ int wave_scan_incl_i(int v) {
+  CASCADE_DPP_SCAN(v, op_add_i, 0, dpp_i32)
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  CASCADE_DPP_SCAN(v, op_add_f, 0.f, dpp_f32)
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-  return v;
+  CASCADE_DPP_SCAN(v, fmaxf, -INFINITY, dpp_f32)
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ int wave_sum_i(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
-  return v;
+  CASCADE_DPP_SCAN(v, op_add_i, 0, dpp_i32)
+  return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+  CASCADE_DPP_SCAN(v, op_min_i, 0x7fffffff, dpp_i32)
+  return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ int wave_max_i(int v) {
+  CASCADE_DPP_SCAN(v, op_max_i, (int)0x80000000, dpp_i32)
+  return __builtin_amdgcn_readlane(v, 63);
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }

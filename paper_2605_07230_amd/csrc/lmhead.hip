@@ -164,7 +164,10 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmParams p) {
 // Operand order: for a block of 32 rows rb and a 16-wide k step ks, 64 x 16 bytes where entry
 // l = (r32, half) holds src[32*rb + r32][16*ks + 8*half .. +7]; the ks blocks of one rb follow
 // each other.  One wave-wide 16-byte load per MFMA operand, 1 KiB contiguous.
-__global__ __launch_bounds__(256) void pack32_kernel(const uint16_t* __restrict__ src, uint4* __restrict__ dst, int rows, int K) {
+__global__ __launch_bounds__(256) void pack32_kernel(const uint16_t* __restrict__ src0, uint4* __restrict__ dst0,
+                                                      const uint16_t* __restrict__ src1, uint4* __restrict__ dst1, int rows, int K) {
+  const uint16_t* src = blockIdx.z ? src1 : src0;
+  uint4* dst = blockIdx.z ? dst1 : dst0;
   const int lane = threadIdx.x & 63, r32 = lane & 31, half = lane >> 5;
   const int ks = blockIdx.x * 4 + (threadIdx.x >> 6), rb = blockIdx.y;
   if (ks >= K / 16) return;
@@ -304,6 +307,126 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
   }
 }
 
+// Eight-wave variant for hidden size 4096: two waves per SIMD (<= 256 registers each), the eight
+// waves split the hidden dimension into 512-wide parts.  A single wave cannot keep the L2 -> CU
+// path busy (measured: 62 GB/s per CU with four waves, 93 GB/s with eight), and the conditional /
+// unconditional hidden states that every workgroup re-reads from L2 are 2/3 of its traffic.
+// Shallower request rings than the four-wave kernel (W 4 steps ahead, H 2), since two waves per
+// SIMD hide each other's waits.  Partial tiles are summed through LDS in two rounds.
+template <bool CFG>
+__global__ __launch_bounds__(512) void lmhead_bf16_packed8_kernel(LmParams p) {
+  constexpr int NA = CFG ? 4 : 2;
+  constexpr int NACC = NA * 2;
+  constexpr int NSTEPS = 32, HD = 2, WD = 4;
+  extern __shared__ float red[];    // [4 waves][NACC][16 regs][64 lanes]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r32 = lane & 31, half = lane >> 5;
+  constexpr int KS = 256;           // k16 steps in the hidden dimension (4096 / 16)
+
+  int logical = blockIdx.x;
+  const int nwg = gridDim.x;
+  if ((nwg & 7) == 0) logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
+  const int ntile = logical / p.n_mchunks, mc = logical % p.n_mchunks;
+  const int v0 = ntile * 64, node0 = mc * 64;
+
+  const uint4* ap[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const uint4* base = (i < 2) ? p.hp_cond : p.hp_uncond;
+    ap[i] = base + ((int64_t)(mc * 2 + (i & 1)) * KS) * 64 + lane;
+  }
+  const uint4* bp[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) bp[j] = (const uint4*)p.w + ((int64_t)(ntile * 2 + j) * KS) * 64 + lane;
+
+  f32x16 acc[NA][2];
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // this wave's k16 steps: 128-wide slices wave, wave + 8, wave + 16, wave + 24
+  auto ks_of_step = [&](int t) { return (wave + 8 * (t >> 3)) * 8 + (t & 7); };
+  Frag8 hr[HD][NA];
+  Frag8 wr[WD][2];
+  auto load_h = [&](int slot, int t) {
+    const int64_t o = (int64_t)ks_of_step(t) * 64;
+#pragma unroll
+    for (int i = 0; i < NA; ++i) hr[slot][i].u = ap[i][o];
+  };
+  auto load_w = [&](int slot, int t) {
+    const int64_t o = (int64_t)ks_of_step(t) * 64;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) wr[slot][j].u = bp[j][o];
+  };
+  // prologue in steady-state request order (..., H(t+HD), W(t+WD), ...)
+#pragma unroll
+  for (int t = 0; t < WD - HD; ++t) load_w(t, t);
+#pragma unroll
+  for (int t = 0; t < HD; ++t) {
+    load_h(t, t);
+    load_w(WD - HD + t, WD - HD + t);
+  }
+#pragma unroll
+  for (int t = 0; t < NSTEPS; ++t) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+        acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hr[t % HD][i].v, wr[t % WD][jj].v, acc[i][jj], 0, 0, 0);
+    if (t + HD < NSTEPS) load_h(t % HD, t + HD);
+    if (t + WD < NSTEPS) load_w(t % WD, t + WD);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // round 1: waves 4..7 hand their partial tiles to waves 0..3
+  if (wave >= 4) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[(((wave - 4) * NACC + i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+  }
+  __syncthreads();
+  if (wave < 4) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] += red[((wave * NACC + i * 2 + j) * 16 + r) * 64 + lane];
+  }
+  __syncthreads();
+  // round 2: waves 0..3 publish, then each of the eight waves finishes half of one 32 x 32 output tile
+  if (wave < 4) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[((wave * NACC + i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+  }
+  __syncthreads();
+  const int tile = wave >> 1, rhalf = wave & 1;   // tile = (node block, column block)
+  const int nbk = tile >> 1, nb = tile & 1;
+#pragma unroll
+  for (int rr = 0; rr < 8; ++rr) {
+    const int r = rhalf * 8 + rr;
+    float c = 0.f, u = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      c += red[((w * NACC + nbk * 2 + nb) * 16 + r) * 64 + lane];
+      if (CFG) u += red[((w * NACC + (2 + nbk) * 2 + nb) * 16 + r) * 64 + lane];
+    }
+    const float gmix = CFG ? u + p.cfg_scale * (c - u) : c;
+    const int node = node0 + 32 * nbk + 8 * (r >> 2) + 4 * half + (r & 3);
+    if (node < p.n_nodes) p.logits[(int64_t)node * p.vocab + v0 + 32 * nb + r32] = gmix / p.temperature;
+  }
+}
+
 // ------------------------------------------------------------------------------------ row stats
 // One workgroup of 1024 threads per row; the row lives in registers (VPT values per thread).
 // row_max, exact k-th largest (radix select on order-preserving integer keys), and log-sum-exp
@@ -316,31 +439,37 @@ __device__ __forceinline__ float key_f32(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-__device__ __forceinline__ int wave_scan_incl_i(int v, int lane) {
+// Exact k-th largest by three rounds of radix selection over the order-preserving keys held in
+// registers: a 4096-bin LDS histogram (integer atomics) of key bits 31..20, then 1024 bins of bits
+// 19..10 among the keys of the chosen bin, then 1024 bins of bits 9..0.  After each round a scan
+// from the top bin finds the bin that holds the k-th largest and how many keys lie above it.
+// (A row whose entries all share one bin, e.g. all equal, serialises on one LDS address: slow, exact.)
+template <int BPT>   // bins per thread; the workgroup's 1024 threads cover 1024 * BPT bins, highest first
+__device__ __forceinline__ void find_bin_from_top(const int* hist, int k, int tid, int lane, int wave, int* s_wsum, int* s_bin,
+                                                  int* s_above) {
+  constexpr int NB = 1024 * BPT;
+  int hb[BPT], loc = 0;
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(v, o, WAVE);
-    if (lane >= o) v += t;
+  for (int i = 0; i < BPT; ++i) { hb[i] = hist[NB - 1 - (BPT * tid + i)]; loc += hb[i]; }
+  const int incl = wave_scan_incl_i(loc);
+  if (lane == 63) s_wsum[wave] = incl;
+  __syncthreads();
+  int before = incl - loc;
+  for (int w = 0; w < wave; ++w) before += s_wsum[w];
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) {
+    if (before < k && before + hb[i] >= k) { *s_bin = NB - 1 - (BPT * tid + i); *s_above = before; }
+    before += hb[i];
   }
-  return v;
+  __syncthreads();
 }
-
-// Exact k-th largest in three stages: (1) a 4096-bin histogram of the top 12 key bits (LDS integer
-// atomics) and a scan from the top locate the bin holding the k-th largest; (2) the keys of that
-// bin are compacted into LDS; (3) one wave resolves the remaining 20 bits bit by bit over the few
-// candidates.  If the bin holds more than CAND_MAX keys (degenerate rows, e.g. all equal) the 20
-// bits are resolved by the whole workgroup over its registers instead.
-constexpr int HBINS = 4096, CAND_MAX = 4096;
 
 template <int VPT>
 __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
   __shared__ float fred[16];
-  __shared__ int ired[2][16];
-  __shared__ int hist[HBINS];
-  __shared__ uint32_t cand[CAND_MAX];
+  __shared__ int hist1[4096], hist2[1024], hist3[1024];
   __shared__ int s_wsum[16];
-  __shared__ int s_bin, s_above, s_cnt;
-  __shared__ uint32_t s_thr;
+  __shared__ int s_bin, s_above;
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int V = p.vocab;
   const float* g = p.logits + (int64_t)row * V;
@@ -357,8 +486,9 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
   }
   if (topk) {
 #pragma unroll
-    for (int i = 0; i < HBINS / 1024; ++i) hist[tid + 1024 * i] = 0;
-    if (tid == 0) s_cnt = 0;
+    for (int i = 0; i < 4; ++i) hist1[tid + 1024 * i] = 0;
+    hist2[tid] = 0;
+    hist3[tid] = 0;
   }
   mx = wave_max(mx);
   if (lane == 0) fred[wave] = mx;
@@ -370,61 +500,30 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
   uint32_t thr_key = 0;            // keeps everything
   float thr = -INFINITY;
   if (topk) {
+    int k = p.top_k;
 #pragma unroll
     for (int i = 0; i < VPT; ++i)
-      if (tid + 1024 * i < V) atomicAdd(&hist[key[i] >> 20], 1);
+      if (tid + 1024 * i < V) atomicAdd(&hist1[key[i] >> 20], 1);
     __syncthreads();
-    // thread t owns the bins 4095-4t .. 4095-4t-3 (counting down from the largest keys)
-    int hb[4], loc = 0;
+    find_bin_from_top<4>(hist1, k, tid, lane, wave, s_wsum, &s_bin, &s_above);
+    const uint32_t b1 = (uint32_t)s_bin;
+    k -= s_above;
+    __syncthreads();   // s_bin / s_above are rewritten by the next round
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { hb[i] = hist[HBINS - 1 - (4 * tid + i)]; loc += hb[i]; }
-    const int incl = wave_scan_incl_i(loc, lane);
-    if (lane == 63) s_wsum[wave] = incl;
+    for (int i = 0; i < VPT; ++i)
+      if (tid + 1024 * i < V && (key[i] >> 20) == b1) atomicAdd(&hist2[(key[i] >> 10) & 1023u], 1);
     __syncthreads();
-    int before = incl - loc;
-    for (int w = 0; w < wave; ++w) before += s_wsum[w];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (before < p.top_k && before + hb[i] >= p.top_k) { s_bin = HBINS - 1 - (4 * tid + i); s_above = before; }
-      before += hb[i];
-    }
+    find_bin_from_top<1>(hist2, k, tid, lane, wave, s_wsum, &s_bin, &s_above);
+    const uint32_t b12 = (b1 << 10) | (uint32_t)s_bin;
+    k -= s_above;
     __syncthreads();
-    const int bin = s_bin, k2 = p.top_k - s_above, n2 = hist[bin];
-    uint32_t prefix = (uint32_t)bin << 20;
-    if (n2 <= CAND_MAX) {
 #pragma unroll
-      for (int i = 0; i < VPT; ++i)
-        if (tid + 1024 * i < V && (int)(key[i] >> 20) == bin) cand[atomicAdd(&s_cnt, 1)] = key[i];
-      __syncthreads();
-      if (wave == 0) {
-        for (int bit = 19; bit >= 0; --bit) {
-          const uint32_t c = prefix | (1u << bit);
-          int cnt = 0;
-          for (int e = lane; e < n2; e += 64) cnt += cand[e] >= c;
-          cnt = wave_sum_i(cnt);
-          if (cnt >= k2) prefix = c;
-        }
-        if (lane == 0) s_thr = prefix;
-      }
-      __syncthreads();
-      prefix = s_thr;
-    } else {
-      for (int bit = 19; bit >= 0; --bit) {
-        const uint32_t c = prefix | (1u << bit);
-        int cnt = 0;
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) cnt += __popcll(__ballot(tid + 1024 * i < V && key[i] >= c));
-        const int buf = bit & 1;
-        if (lane == 0) ired[buf][wave] = cnt;
-        __syncthreads();
-        int tot = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) tot += ired[buf][w];
-        if (tot >= p.top_k) prefix = c;
-      }
-    }
-    thr_key = prefix;
-    thr = key_f32(prefix);
+    for (int i = 0; i < VPT; ++i)
+      if (tid + 1024 * i < V && (key[i] >> 10) == b12) atomicAdd(&hist3[key[i] & 1023u], 1);
+    __syncthreads();
+    find_bin_from_top<1>(hist3, k, tid, lane, wave, s_wsum, &s_bin, &s_above);
+    thr_key = (b12 << 10) | (uint32_t)s_bin;
+    thr = key_f32(thr_key);
   }
   float se = 0.f;
 #pragma unroll
@@ -478,10 +577,11 @@ hipError_t launch_lmhead_f32(cascade_ctx* ctx, const lmhead_args* a) {
   return hipGetLastError();
 }
 
-template <bool CFG, int KIND>   // KIND 0: row-major W, 1: packed, 2: packed with the deep pipeline
+template <bool CFG, int KIND>   // KIND 0: row-major W, 1: packed, 2: packed + deep pipeline (4 waves), 3: packed, 8 waves
 hipError_t launch_bf16_gemm(cascade_ctx* ctx, const LmParams& p, int grid) {
   const size_t smem = (size_t)4 * (CFG ? 8 : 4) * 16 * 64 * sizeof(float);
-  auto kern = KIND == 2 ? lmhead_bf16_packed_kernel<CFG, 64> : (KIND == 1 ? lmhead_bf16_packed_kernel<CFG, 0> : lmhead_bf16_kernel<CFG>);
+  auto kern = KIND == 3 ? lmhead_bf16_packed8_kernel<CFG>
+                        : (KIND == 2 ? lmhead_bf16_packed_kernel<CFG, 64> : (KIND == 1 ? lmhead_bf16_packed_kernel<CFG, 0> : lmhead_bf16_kernel<CFG>));
   static bool attr_done = false;   // one flag per template instance
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -489,7 +589,7 @@ hipError_t launch_bf16_gemm(cascade_ctx* ctx, const LmParams& p, int grid) {
     attr_done = true;
   }
   KernelTimer t(ctx, CASCADE_K_LMHEAD);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, ctx->stream, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(KIND == 3 ? 512 : 256), smem, ctx->stream, p);
   return hipGetLastError();
 }
 
@@ -504,14 +604,14 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
     if (per * 2 > ctx->hpack_ws_bytes) return hipErrorInvalidValue;
     uint4* hc = (uint4*)ctx->hpack_ws;
     uint4* hu = (uint4*)(ctx->hpack_ws + per);
-    dim3 pgrid((a->hidden / 16 + 3) / 4, rblocks);
-    hipLaunchKernelGGL(pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_cond, hc, a->n_nodes, a->hidden);
-    if (cfg) hipLaunchKernelGGL(pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_uncond, hu, a->n_nodes, a->hidden);
+    dim3 pgrid((a->hidden / 16 + 3) / 4, rblocks, cfg ? 2 : 1);
+    hipLaunchKernelGGL(pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_cond, hc,
+                       (const uint16_t*)a->h_uncond, hu, a->n_nodes, a->hidden);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     p.hp_cond = hc;
     p.hp_uncond = hu;
-    if (a->hidden == 4096) return cfg ? launch_bf16_gemm<true, 2>(ctx, p, grid) : launch_bf16_gemm<false, 2>(ctx, p, grid);
+    if (a->hidden == 4096) return cfg ? launch_bf16_gemm<true, 3>(ctx, p, grid) : launch_bf16_gemm<false, 3>(ctx, p, grid);
     return cfg ? launch_bf16_gemm<true, 1>(ctx, p, grid) : launch_bf16_gemm<false, 1>(ctx, p, grid);
   }
   return cfg ? launch_bf16_gemm<true, 0>(ctx, p, grid) : launch_bf16_gemm<false, 0>(ctx, p, grid);
@@ -519,7 +619,8 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
 
 hipError_t launch_pack_w(cascade_ctx* ctx, const void* w, int vocab, int hidden, void* w_packed) {
   dim3 grid((hidden / 16 + 3) / 4, vocab / 32);
-  hipLaunchKernelGGL(pack32_kernel, grid, dim3(256), 0, ctx->stream, (const uint16_t*)w, (uint4*)w_packed, vocab, hidden);
+  hipLaunchKernelGGL(pack32_kernel, grid, dim3(256), 0, ctx->stream, (const uint16_t*)w, (uint4*)w_packed,
+                     (const uint16_t*)nullptr, (uint4*)nullptr, vocab, hidden);
   return hipGetLastError();
 }
 

@@ -14,23 +14,10 @@
 
 namespace {
 
-constexpr int SEL_THREADS = 512;
-constexpr int SEL_WAVES = SEL_THREADS / 64;
-constexpr int MAXCH = CASCADE_MAX_TREE / 64;
 constexpr int MAXCHUNKS = CASCADE_MAX_VOCAB / 256;
 
 __device__ __forceinline__ float readlane_f(float v, int l) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
-}
-
-// inclusive scan over the wave
-__device__ __forceinline__ float wave_scan_incl(float v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const float t = __shfl_up(v, o, WAVE);
-    if (lane >= o) v += t;
-  }
-  return v;
 }
 
 struct Try {
@@ -48,7 +35,12 @@ __device__ __forceinline__ Try try_node(float q, float mi, float mc, float up, f
   return r;
 }
 
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int* dev_status) {
+// NT = threads; TCH = 64-node chunks of the tree held in registers by the walking wave
+// (Tn <= 64 * TCH); CPW = 256-entry vocabulary chunks each wave keeps in registers
+// (V <= 256 * (NT / 64) * CPW)
+template <int NT, int TCH, int CPW>
+__global__ __launch_bounds__(NT) void select_kernel(select_args a, int* dev_status) {
+  constexpr int SEL_THREADS = NT, SEL_WAVES = NT / 64;
   __shared__ int s_path[CASCADE_MAX_DEPTH];
   __shared__ int s_tried[CASCADE_MAX_WIDTH];
   __shared__ int s_len, s_cur, s_ntried, s_best;
@@ -63,17 +55,17 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
-  const int lo = a.node_off[b], Tn = min(a.node_off[b + 1] - lo, CASCADE_MAX_TREE);
+  const int lo = a.node_off[b], Tn = min(a.node_off[b + 1] - lo, 64 * TCH);
   const int maxd = min(a.max_depth, CASCADE_MAX_DEPTH);
   const float eps = a.eps_tvd;
 
   if (a.mode == CASCADE_WALK_SEQUENTIAL) {
     if (wave == 0) {
       const int nch = (Tn + 63) >> 6;
-      int par[MAXCH], tok[MAXCH];
-      float qv[MAXCH], mi[MAXCH], mc[MAXCH], up[MAXCH];
+      int par[TCH], tok[TCH];
+      float qv[TCH], mi[TCH], mc[TCH], up[TCH];
 #pragma unroll
-      for (int c = 0; c < MAXCH; ++c) {
+      for (int c = 0; c < TCH; ++c) {
         const int j = c * 64 + lane;
         par[c] = -2; tok[c] = -1; qv[c] = 0.f; mi[c] = 0.f; mc[c] = 0.f; up[c] = 0.f;
         if (c < nch && j < Tn) {
@@ -91,7 +83,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
         int accepted = -1;
         ntried = 0;
 #pragma unroll
-        for (int c = 0; c < MAXCH; ++c) {
+        for (int c = 0; c < TCH; ++c) {
           if (c < nch && accepted < 0) {
             const int j = c * 64 + lane;
             unsigned long long kids = __ballot(par[c] == cur && j > cur);
@@ -134,15 +126,15 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
     for (int i = tid; i < Tn; i += SEL_THREADS)
       if (s_par[i] >= 0) s_haschild[s_par[i]] = 1;
     for (int round = 0; round < maxd; ++round) {
-      bool can[CASCADE_MAX_TREE / SEL_THREADS];
+      bool can[(CASCADE_MAX_TREE + SEL_THREADS - 1) / SEL_THREADS];
 #pragma unroll
-      for (int k = 0; k < CASCADE_MAX_TREE / SEL_THREADS; ++k) {
+      for (int k = 0; k < (CASCADE_MAX_TREE + SEL_THREADS - 1) / SEL_THREADS; ++k) {
         const int i = tid + k * SEL_THREADS;
         can[k] = i < Tn && !s_ready[i] && s_par[i] >= 0 && s_ready[s_par[i]];
       }
       __syncthreads();
 #pragma unroll
-      for (int k = 0; k < CASCADE_MAX_TREE / SEL_THREADS; ++k) {
+      for (int k = 0; k < (CASCADE_MAX_TREE + SEL_THREADS - 1) / SEL_THREADS; ++k) {
         const int i = tid + k * SEL_THREADS;
         if (can[k]) {
           const int pi = s_par[i];
@@ -198,33 +190,63 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
   const bool vec = (V & 3) == 0;
   const float ub = a.u_bonus[b];
 
-  // masses of the 4 entries a lane owns inside a chunk
-  auto chunk_vals = [&](int c, bool use_ban, float r[4]) {
+  // every wave owns the chunks wave, wave + NW, ...; their logits are loaded in batches of 8 chunks
+  // (all loads of a batch in flight together).  With a single batch (CPW == 8) the registers are
+  // kept, and the crossing chunk is later resolved by its owner without a second trip to memory.
+  constexpr int NBATCH = CPW / 8;
+  auto load_chunk = [&](int c) -> f32x4 {
     const int e0 = c * 256 + lane * 4;
-    float gv[4];
-    if (vec && e0 + 3 < V) {
-      const f32x4 t = *(const f32x4*)(Lr + e0);
-      gv[0] = t[0]; gv[1] = t[1]; gv[2] = t[2]; gv[3] = t[3];
-    } else {
+    f32x4 v = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    if (c < nchunks) {
+      if (vec && e0 + 3 < V) {
+        v = *(const f32x4*)(Lr + e0);
+      } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) gv[i] = e0 + i < V ? Lr[e0 + i] : -INFINITY;
+        for (int i = 0; i < 4; ++i) if (e0 + i < V) v[i] = Lr[e0 + i];
+      }
     }
+    return v;
+  };
+  f32x4 gv[8];
+  if (NBATCH == 1) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      bool keep = gv[i] >= thr && e0 + i < V;
-      if (keep && use_ban)
-        for (int e = 0; e < ntried; ++e) keep = keep && (s_tried[e] != e0 + i);
-      r[i] = keep ? __expf(gv[i] - lse) : 0.f;
+    for (int ci = 0; ci < 8; ++ci) gv[ci] = load_chunk(wave + SEL_WAVES * ci);
+  }
+  // masses of the 4 entries a lane owns inside chunk c
+  // lane e holds the e-th rejected token; chunk_vals visits them with readlane (no LDS in the loop)
+  const int tried_reg = lane < ntried ? s_tried[lane] : -1;
+  auto chunk_vals = [&](int c, const f32x4& g4, bool use_ban, float r[4]) {
+    const int e0 = c * 256 + lane * 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = (g4[i] >= thr && e0 + i < V) ? __expf(g4[i] - lse) : 0.f;
+    if (use_ban) {
+      for (int e = 0; e < ntried; ++e) {
+        const int t = __builtin_amdgcn_readlane(tried_reg, e);
+        if ((t >> 8) == c && lane == ((t & 255) >> 2)) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) if ((t & 3) == i) r[i] = 0.f;
+        }
+      }
     }
   };
 
   bool use_ban = true;
   for (int attempt = 0; attempt < 2; ++attempt) {
-    for (int c = wave; c < nchunks; c += SEL_WAVES) {
-      float r[4];
-      chunk_vals(c, use_ban, r);
-      const float cs = wave_sum(((r[0] + r[1]) + r[2]) + r[3]);
-      if (lane == 0) s_chunk[c] = cs;
+    for (int bt = 0; bt < NBATCH; ++bt) {
+      if (NBATCH > 1) {
+#pragma unroll
+        for (int ci = 0; ci < 8; ++ci) gv[ci] = load_chunk(wave + SEL_WAVES * (8 * bt + ci));
+      }
+#pragma unroll
+      for (int ci = 0; ci < 8; ++ci) {
+        const int c = wave + SEL_WAVES * (8 * bt + ci);
+        if (c < nchunks) {
+          float r[4];
+          chunk_vals(c, gv[ci], use_ban, r);
+          const float cs = wave_sum(((r[0] + r[1]) + r[2]) + r[3]);
+          if (lane == 0) s_chunk[c] = cs;
+        }
+      }
     }
     __syncthreads();
     if (wave == 0) {
@@ -235,8 +257,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
         cs[i] = 4 * lane + i < nchunks ? s_chunk[4 * lane + i] : 0.f;
         loc += cs[i];
       }
-      const float incl = wave_scan_incl(loc, lane);
-      const float total = __shfl(incl, 63, WAVE);
+      const float incl = wave_scan_incl_f(loc);
+      const float total = readlane_f(incl, 63);
       const float target = ub * total;
       float run = incl - loc;
       int cand = 0x7fffffff;
@@ -246,16 +268,13 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
         if (cand == 0x7fffffff && cs[i] > 0.f && run + cs[i] > target) { cand = 4 * lane + i; cbase = run; }
         run += cs[i];
       }
-      int best = cand;
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) best = min(best, __shfl_xor(best, o, WAVE));
+      const int best = wave_min_i(cand);
       if (best == 0x7fffffff) {
         // rounding kept the running sum at or below the target: take the last chunk that holds mass
         int lastc = -1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) if (cs[i] > 0.f) lastc = 4 * lane + i;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) lastc = max(lastc, __shfl_xor(lastc, o, WAVE));
+        lastc = wave_max_i(lastc);
         if (lane == 0) { s_cstar = lastc; s_base = 0.f; s_lastkept = 1; }
       } else if (cand == best) {
         s_cstar = best;
@@ -270,37 +289,40 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
     __syncthreads();
   }
 
-  if (wave == 0) {
+  {
     const int cstar = s_cstar;
-    int x = -1;
-    if (s_total > 0.f && cstar >= 0) {
-      const float target = ub * s_total;
-      float r[4];
-      chunk_vals(cstar, use_ban, r);
-      const float p0 = r[0], p1 = p0 + r[1], p2 = p1 + r[2], p3 = p2 + r[3];
-      const float incl = wave_scan_incl(p3, lane);
-      const float run = s_base + (incl - p3);
-      int cand = 0x7fffffff;
-      const int e0 = cstar * 256 + lane * 4;
-      if (r[0] > 0.f && run + p0 > target) cand = e0;
-      else if (r[1] > 0.f && run + p1 > target) cand = e0 + 1;
-      else if (r[2] > 0.f && run + p2 > target) cand = e0 + 2;
-      else if (r[3] > 0.f && run + p3 > target) cand = e0 + 3;
-      int best = s_lastkept ? 0x7fffffff : cand;
+    const bool ok = s_total > 0.f && cstar >= 0;
+    if (!ok && tid == 0) a.emitted[(int64_t)b * (a.max_depth + 1) + len] = -1;
 #pragma unroll
-      for (int o = 32; o > 0; o >>= 1) best = min(best, __shfl_xor(best, o, WAVE));
-      if (best != 0x7fffffff) {
-        x = best;
-      } else {
-        int last = -1;
+    for (int ci = 0; ci < 8; ++ci) {
+      // the owner of the crossing chunk finishes (kept registers, or one reload when there were several batches)
+      if (ok && (NBATCH == 1 ? wave + SEL_WAVES * ci == cstar : (ci == 0 && wave == cstar % SEL_WAVES))) {
+        const float target = ub * s_total;
+        float r[4];
+        const f32x4 g4 = NBATCH == 1 ? gv[ci] : load_chunk(cstar);
+        chunk_vals(cstar, g4, use_ban, r);
+        const float p0 = r[0], p1 = p0 + r[1], p2 = p1 + r[2], p3 = p2 + r[3];
+        const float incl = wave_scan_incl_f(p3);
+        const float run = s_base + (incl - p3);
+        int cand = 0x7fffffff;
+        const int e0 = cstar * 256 + lane * 4;
+        if (!s_lastkept) {
+          if (r[0] > 0.f && run + p0 > target) cand = e0;
+          else if (r[1] > 0.f && run + p1 > target) cand = e0 + 1;
+          else if (r[2] > 0.f && run + p2 > target) cand = e0 + 2;
+          else if (r[3] > 0.f && run + p3 > target) cand = e0 + 3;
+        }
+        const int best = wave_min_i(cand);
+        int x = best;
+        if (best == 0x7fffffff) {
+          int last = -1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) if (r[i] > 0.f) last = e0 + i;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, WAVE));
-        x = last;
+          for (int i = 0; i < 4; ++i) if (r[i] > 0.f) last = e0 + i;
+          x = wave_max_i(last);
+        }
+        if (lane == 0) a.emitted[(int64_t)b * (a.max_depth + 1) + len] = x;
       }
     }
-    if (lane == 0) a.emitted[(int64_t)b * (a.max_depth + 1) + len] = x;
   }
   for (int d = tid; d < a.max_depth; d += SEL_THREADS)
     a.path_nodes[(int64_t)b * a.max_depth + d] = d < len ? s_path[d] : -1;
@@ -319,6 +341,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(select_args a, int*
 
 hipError_t launch_select(cascade_ctx* ctx, const select_args* a) {
   KernelTimer t(ctx, CASCADE_K_SELECT);
-  hipLaunchKernelGGL(select_kernel, dim3(a->n_prompts), dim3(SEL_THREADS), 0, ctx->stream, *a, ctx->dev_status);
+  const bool small_tree = ctx->lim.max_nodes_per_tree <= 256, small_vocab = a->vocab <= 16384;
+  dim3 grid(a->n_prompts);
+  if (small_tree && small_vocab) hipLaunchKernelGGL((select_kernel<512, 4, 8>), grid, dim3(512), 0, ctx->stream, *a, ctx->dev_status);
+  else if (small_tree) hipLaunchKernelGGL((select_kernel<1024, 4, 16>), grid, dim3(1024), 0, ctx->stream, *a, ctx->dev_status);
+  else if (small_vocab) hipLaunchKernelGGL((select_kernel<512, 16, 8>), grid, dim3(512), 0, ctx->stream, *a, ctx->dev_status);
+  else hipLaunchKernelGGL((select_kernel<1024, 16, 16>), grid, dim3(1024), 0, ctx->stream, *a, ctx->dev_status);
   return hipGetLastError();
 }
