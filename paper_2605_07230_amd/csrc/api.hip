@@ -61,8 +61,8 @@ int cascade_create(cascade_ctx** out, const cascade_limits* lim, void* hip_strea
   const size_t cap = (size_t)256 << 20;
   if (attn > cap) attn = cap;
   c->attn_ws_bytes = align_up(attn, 256);
-  // packed hidden states: two operands (cond, uncond), rows rounded up to 64, 2 bytes per element
-  c->hpack_ws_bytes = align_up((size_t)2 * ((lim->max_nodes_total + 63) / 64 * 64) * lim->hidden * 2, 256);
+  // packed hidden states: two operands (cond, uncond), rows rounded up to 256, 2 bytes per element
+  c->hpack_ws_bytes = align_up((size_t)2 * ((lim->max_nodes_total + 255) / 256 * 256) * lim->hidden * 2, 256);
   const size_t imask_bytes = align_up((size_t)lim->max_nodes_total * 8, 256);
   c->ws_bytes = 256 + c->attn_ws_bytes + c->hpack_ws_bytes + imask_bytes;
   e = hipMalloc((void**)&c->ws, c->ws_bytes);

@@ -55,9 +55,11 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(LmParams p) {
 }
 
 // ----------------------------------------------------------------------------------------- bf16
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 union Frag8 {
   bf16x8 v;
   uint4 u;
+  u32x4 n;
 };
 
 template <bool CFG>
@@ -427,6 +429,130 @@ __global__ __launch_bounds__(512) void lmhead_bf16_packed8_kernel(LmParams p) {
   }
 }
 
+// ------------------------------------------------------------------- bf16, packed, many rows
+// LDS-tiled projection for steps with several hundred rows (batched prompts), where the kernel is
+// bound by the matrix cores instead of by streaming W.  Workgroup tile = 256 rows x 256 vocabulary
+// columns: with guidance 128 nodes (4 conditional + 4 unconditional 32-row blocks), without 256
+// nodes.  The four waves form a 2 x 2 grid; a wave owns 4 row blocks (two node blocks, conditional
+// and unconditional, so the mix stays in registers) x 4 column blocks = 16 accumulators.  Both
+// operands arrive packed in MFMA operand order, so global -> register -> LDS -> register moves are
+// all contiguous 16-byte pieces in lane order (no bank conflicts, no shuffles).  Stages of four
+// k16 steps (64 KiB) are double-buffered in LDS; the next stage's global loads are issued before
+// the current stage's MFMAs.
+template <bool CFG>
+__global__ __launch_bounds__(256) void lmhead_bf16_tiled_kernel(LmParams p, int n_mtiles) {
+  extern __shared__ u32x4 lds[];     // [2 stages][4 k16 steps][16 blocks: 8 A then 8 B][64 lanes]
+  constexpr int BK = 4, STAGE = BK * 16 * 64;   // uint4 per stage
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r32 = lane & 31, half = lane >> 5;
+  const int KS = p.hidden / 16, n_stages = KS / BK;
+
+  int logical = blockIdx.x;
+  const int nwg = gridDim.x;
+  if ((nwg & 7) == 0) logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
+  const int nt = logical / n_mtiles, mt = logical % n_mtiles;
+
+  // loader: piece q = tid + 256 i -> k16 step i / 4, block wave + 4 (i % 4), lane: a wave always copies
+  // whole 1 KiB blocks, and a thread needs only four base pointers (one per block it serves)
+  const u32x4* src[4];
+#pragma unroll
+  for (int b4 = 0; b4 < 4; ++b4) {
+    const int blk = wave + 4 * b4;
+    const u32x4* base;
+    int64_t rb;   // 32-row block index in the source matrix
+    if (blk < 8) {
+      if (CFG) { base = (const u32x4*)(blk < 4 ? p.hp_cond : p.hp_uncond); rb = (int64_t)mt * 4 + (blk & 3); }
+      else { base = (const u32x4*)p.hp_cond; rb = (int64_t)mt * 8 + blk; }
+    } else {
+      base = (const u32x4*)p.w;
+      rb = (int64_t)nt * 8 + (blk - 8);
+    }
+    src[b4] = base + rb * KS * 64 + lane;
+  }
+  // two register sets: while stage st is multiplied out of LDS, stage st+1 sits in one set (arrived,
+  // about to be written to the other LDS buffer) and stage st+2 is in flight into the other set —
+  // 128 KiB of requests per CU, which is what it takes to cover the L2 / HBM latency at this rate
+  u32x4 stg[2][16];
+  auto request_stage = [&](int set, int st) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) stg[set][i] = src[i & 3][((int64_t)st * BK + (i >> 2)) * 64];
+  };
+  auto store_stage = [&](int set, int buf) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) lds[buf * STAGE + tid + 256 * i] = stg[set][i];
+  };
+
+  const int wm = wave >> 1, wn = wave & 1;
+  int ablk[4];
+  if (CFG) { ablk[0] = 2 * wm; ablk[1] = 2 * wm + 1; ablk[2] = 4 + 2 * wm; ablk[3] = 5 + 2 * wm; }
+  else { ablk[0] = 4 * wm; ablk[1] = 4 * wm + 1; ablk[2] = 4 * wm + 2; ablk[3] = 4 * wm + 3; }
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // operand fragments are double-buffered in registers: step ks+1 is read from LDS while step ks multiplies
+  Frag8 fa[2][4], fb[2][4];
+  auto read_frags = [&](int slot, int buf, int ks) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[slot][i].n = lds[buf * STAGE + (ks * 16 + ablk[i]) * 64 + lane];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fb[slot][j].n = lds[buf * STAGE + (ks * 16 + 8 + 4 * wn + j) * 64 + lane];
+  };
+  auto compute_stage = [&](int buf, int set_to_store) {
+#pragma unroll
+    for (int ks = 0; ks < BK; ++ks) {
+      if (ks + 1 < BK) read_frags((ks + 1) & 1, buf, ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i].v, fb[ks & 1][j].v, acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      // the other LDS buffer was released by the barrier that ended the previous iteration; fill it
+      // while the matrix cores work through this stage
+      if (ks == 1) store_stage(set_to_store, buf ^ 1);
+    }
+    __syncthreads();
+    read_frags(0, buf ^ 1, 0);
+  };
+  // stage indices past the end are clamped: redundant loads and LDS writes, but no branches
+  const int last = n_stages - 1;
+  request_stage(0, 0);
+  request_stage(1, min(1, last));
+  store_stage(0, 0);
+  __syncthreads();
+  read_frags(0, 0, 0);
+  for (int st = 0; st < n_stages; st += 2) {   // n_stages is even (hidden is a multiple of 128)
+    request_stage(0, min(st + 2, last));
+    compute_stage(0, 1);                        // multiplies stage st, writes stage st+1 (set 1) to LDS buffer 1
+    request_stage(1, min(st + 3, last));
+    compute_stage(1, 0);                        // multiplies stage st+1, writes stage st+2 (set 0) to LDS buffer 0
+  }
+
+  // epilogue: accumulator (i, j), register r of lane (r32, half) is row 8 (r / 4) + 4 half + r % 4, column r32
+  const int v0 = nt * 256 + 128 * wn;
+#pragma unroll
+  for (int i = 0; i < (CFG ? 2 : 4); ++i) {
+    const int node0 = CFG ? mt * 128 + 32 * (2 * wm + i) : mt * 256 + 32 * (4 * wm + i);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float c = acc[i][j][r];
+        const float gmix = CFG ? acc[i + 2][j][r] + p.cfg_scale * (c - acc[i + 2][j][r]) : c;
+        const int node = node0 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (node < p.n_nodes) p.logits[(int64_t)node * p.vocab + v0 + 32 * j + r32] = gmix / p.temperature;
+        if (r == 15) __builtin_amdgcn_sched_barrier(0);   // one accumulator pair at a time leaves the AGPRs
+      }
+  }
+}
+
 // ------------------------------------------------------------------------------------ row stats
 // One workgroup of 1024 threads per row; the row lives in registers (VPT values per thread).
 // row_max, exact k-th largest (radix select on order-preserving integer keys), and log-sum-exp
@@ -598,8 +724,13 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
   const int grid = (a->vocab / 64) * p.n_mchunks;
   const bool cfg = a->h_uncond != nullptr;
   if (a->w_layout == CASCADE_W_PACKED32) {
-    // repack this step's hidden states into operand order (rows rounded up to 64 per operand)
-    const int rblocks = p.n_mchunks * 2;
+    // many rows and a vocabulary made of whole 256-column tiles: LDS-tiled kernel, 256-row tiles
+    const int rows = a->n_nodes * (cfg ? 2 : 1);
+    const bool tiled = rows >= 512 && (a->vocab % 256) == 0;
+    const int nodes_per_tile = cfg ? 128 : 256;
+    const int n_mtiles = (a->n_nodes + nodes_per_tile - 1) / nodes_per_tile;
+    // repack this step's hidden states into operand order (zero rows up to a whole tile / chunk)
+    const int rblocks = tiled ? n_mtiles * (nodes_per_tile / 32) : p.n_mchunks * 2;
     const size_t per = (size_t)rblocks * 32 * a->hidden * 2;
     if (per * 2 > ctx->hpack_ws_bytes) return hipErrorInvalidValue;
     uint4* hc = (uint4*)ctx->hpack_ws;
@@ -611,7 +742,20 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
     if (e != hipSuccess) return e;
     p.hp_cond = hc;
     p.hp_uncond = hu;
-    if (a->hidden == 4096) return cfg ? launch_bf16_gemm<true, 3>(ctx, p, grid) : launch_bf16_gemm<false, 3>(ctx, p, grid);
+    if (tiled) {
+      const size_t smem = (size_t)2 * 4 * 16 * 64 * sizeof(uint4);   // 128 KiB
+      static bool attr_done[2] = {false, false};
+      auto kern = cfg ? lmhead_bf16_tiled_kernel<true> : lmhead_bf16_tiled_kernel<false>;
+      if (!attr_done[cfg]) {
+        e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_done[cfg] = true;
+      }
+      KernelTimer t(ctx, CASCADE_K_LMHEAD);
+      hipLaunchKernelGGL(kern, dim3((a->vocab / 256) * n_mtiles), dim3(256), smem, ctx->stream, p, n_mtiles);
+      return hipGetLastError();
+    }
+    if (a->hidden == 4096) return cfg ? launch_bf16_gemm<true, 2>(ctx, p, grid) : launch_bf16_gemm<false, 2>(ctx, p, grid);
     return cfg ? launch_bf16_gemm<true, 1>(ctx, p, grid) : launch_bf16_gemm<false, 1>(ctx, p, grid);
   }
   return cfg ? launch_bf16_gemm<true, 0>(ctx, p, grid) : launch_bf16_gemm<false, 0>(ctx, p, grid);
