@@ -119,16 +119,6 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnParams p, int n_rows,
 // ----------------------------------------------------------------------------------------- bf16
 constexpr int KT = 64;  // keys per tile
 
-template <int D>
-struct AttnSmem {
-  static constexpr int KP = D + 8;     // K row pitch (elements)
-  static constexpr int VP = KT + 4;    // V^T row pitch (elements): 136 B, conflict-free 8-byte reads
-  uint16_t k[KT * KP];
-  uint16_t vt[D * VP];
-  int parent[CASCADE_MAX_TREE];
-  unsigned long long anc[256];
-};
-
 // two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -145,14 +135,33 @@ union Frag8 {
   uint2 h[2];
 };
 
-// NQ = 16-row query blocks per wave (the workgroup covers 64*NQ query rows).
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+struct TileSmem {
+  static constexpr int KP = D + 8;      // K row pitch (elements)
+  static constexpr int VP = D + 16;     // V row pitch (elements): 4 consecutive keys fall on distinct bank groups
+  uint16_t k[KT * KP];
+  uint16_t v[KT * VP];
+};
+
+// Large trees.  Workgroup = (row, kv head, 64*NQ query rows, kv split); its four waves own NQ 16-row
+// query blocks each and share every 64-key K/V tile through LDS.  Tiles are double-buffered in LDS
+// and prefetched through registers: while tile t is multiplied, tile t+1 is written to the other
+// buffer and tile t+2 is in flight from HBM, with one workgroup barrier per tile.  K and V are
+// stored row-major; the V^T operand is fetched with the transposing LDS read.
 template <int D, int NQ, bool SPLIT>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
-  using SM = AttnSmem<D>;
-  __shared__ SM sm;
+  using TS = TileSmem<D>;
+  extern __shared__ __align__(16) char smem_raw[];
+  TS* tiles = (TS*)smem_raw;                                                    // [2]
+  int* s_parent = (int*)(smem_raw + 2 * sizeof(TS));                            // [CASCADE_MAX_TREE]
+  unsigned long long* s_anc = (unsigned long long*)(s_parent + CASCADE_MAX_TREE);   // [2][256]
   constexpr int KS = D / 32;   // 32-wide d steps of the score MFMA
   constexpr int DB = D / 16;   // 16-wide d blocks of the output
   constexpr int DC = D / 8;    // 16-byte chunks per row
+  constexpr int NPC = KT * DC / 256;   // 16-byte pieces of K (and of V) per thread per tile
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   const int s = blockIdx.z, kvh = blockIdx.y;
@@ -174,6 +183,52 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
   const uint16_t* vtr = (const uint16_t*)p.v_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D;
   const int64_t tree_pitch = (int64_t)p.n_kv_heads * D;
 
+  // tile staging registers: piece c = tid + 256 it -> key c / DC, 8 d at c % DC
+  u32x4 kr[NPC], vr[NPC];
+  auto request_tile = [&](int t) {
+    const bool tree_tile = t >= n_pt;
+    const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
+    const int klimit = tree_tile ? T : P;
+    const uint16_t* ksrc = tree_tile ? ktr : kc;
+    const uint16_t* vsrc = tree_tile ? vtr : vc;
+    const int64_t pitch = tree_tile ? tree_pitch : p.sp;
+#pragma unroll
+    for (int it = 0; it < NPC; ++it) {
+      const int c = tid + 256 * it, key = c / DC, dc = c % DC;
+      kr[it] = u32x4{0u, 0u, 0u, 0u};
+      vr[it] = u32x4{0u, 0u, 0u, 0u};
+      if (t < t_end && kbase + key < klimit) {
+        kr[it] = *(const u32x4*)(ksrc + (int64_t)(kbase + key) * pitch + 8 * dc);
+        vr[it] = *(const u32x4*)(vsrc + (int64_t)(kbase + key) * pitch + 8 * dc);
+      }
+    }
+  };
+  // registers -> LDS buffer, plus (tree tiles) one ancestor-or-self word per query row of the workgroup
+  auto store_tile = [&](int t, int buf) {
+#pragma unroll
+    for (int it = 0; it < NPC; ++it) {
+      const int c = tid + 256 * it, key = c / DC, dc = c % DC;
+      *(u32x4*)(&tiles[buf].k[key * TS::KP + 8 * dc]) = kr[it];
+      *(u32x4*)(&tiles[buf].v[key * TS::VP + 8 * dc]) = vr[it];
+    }
+    if (t < t_end && t >= n_pt && tid < 64 * NQ) {
+      const int kbase = (t - n_pt) * KT;
+      const int r = row0 + tid;
+      unsigned long long wbits = 0ull;
+      if (r < M) {
+        int a = r % T, guard = 0;
+        while (a >= 0 && guard++ <= CASCADE_MAX_TREE) {
+          const int rel = a - kbase;
+          if (rel < 0) break;   // ancestors only get smaller
+          if (rel < 64) wbits |= 1ull << rel;
+          a = s_parent[a];
+        }
+      }
+      s_anc[buf * 256 + tid] = wbits;
+    }
+  };
+
+  request_tile(t_begin);   // in flight while parents and queries are fetched
   if (t_end > n_pt) {
     for (int i = tid; i < T; i += 256) {
       int pi = p.parent[lo + i];
@@ -181,20 +236,18 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
         atomicOr(p.dev_status, CASCADE_FLAG_PARENT);
         pi = (i == 0) ? -1 : 0;   // keep the climb finite
       }
-      sm.parent[i] = pi;
+      s_parent[i] = pi;
     }
   }
 
   // query fragments (B operand of S^T): lane = (query l16, d group g)
   Frag8 qf[NQ][KS];
   int64_t out_row[NQ];   // index into [N*Hq] or -1
-  int q_node[NQ];
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
     const int r = row0 + 16 * (wave + 4 * n) + l16;
     const bool ok = r < M;
     const int i = ok ? r % T : 0, hg = ok ? r / T : 0;
-    q_node[n] = ok ? i : -1;
     const int64_t rowg = (int64_t)(lo + i) * p.n_heads + kvh * G + hg;
     out_row[n] = ok ? rowg : -1;
     const uint16_t* qp = (const uint16_t*)p.q + rowg * D + 8 * g;
@@ -215,67 +268,20 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
     for (int db = 0; db < DB; ++db) ot[n][db] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  __syncthreads();               // parent array complete
+  store_tile(t_begin, 0);
+  request_tile(t_begin + 1);
+  __syncthreads();
+
   for (int t = t_begin; t < t_end; ++t) {
+    const int buf = (t - t_begin) & 1;
+    const TS& tl = tiles[buf];
     const bool tree_tile = t >= n_pt;
     const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
     const int klimit = tree_tile ? T : P;
-    const uint16_t* ksrc = tree_tile ? ktr : kc;
-    const uint16_t* vsrc = tree_tile ? vtr : vc;
-    const int64_t pitch = tree_tile ? tree_pitch : p.sp;
-    __syncthreads();   // previous tile fully consumed
-    // K tile, row-major
-#pragma unroll
-    for (int it = 0; it < (KT * DC) / 256; ++it) {
-      const int c = tid + 256 * it;
-      const int key = c / DC, dc = c % DC;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (kbase + key < klimit) v = *(const uint4*)(ksrc + (int64_t)(kbase + key) * pitch + 8 * dc);
-      *(uint4*)(&sm.k[key * SM::KP + 8 * dc]) = v;
-    }
-    // V tile, transposed: a thread takes 4 keys x 8 d and writes 8 rows of 4 keys
-    if (tid < 16 * DC) {
-      const int dc = tid % DC, kg = tid / DC;
-      uint32_t w[4][4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int key = kbase + 4 * kg + r;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (key < klimit) v = *(const uint4*)(vsrc + (int64_t)key * pitch + 8 * dc);
-        w[r][0] = v.x; w[r][1] = v.y; w[r][2] = v.z; w[r][3] = v.w;
-      }
-#pragma unroll
-      for (int dd = 0; dd < 8; ++dd) {
-        const int wi = dd >> 1;
-        uint2 o;
-        if (dd & 1) {
-          o.x = (w[0][wi] >> 16) | (w[1][wi] & 0xffff0000u);
-          o.y = (w[2][wi] >> 16) | (w[3][wi] & 0xffff0000u);
-        } else {
-          o.x = (w[0][wi] & 0xffffu) | (w[1][wi] << 16);
-          o.y = (w[2][wi] & 0xffffu) | (w[3][wi] << 16);
-        }
-        *(uint2*)(&sm.vt[(8 * dc + dd) * SM::VP + 4 * kg]) = o;
-      }
-    }
-    if (tree_tile) {
-      // ancestor-or-self bits of the tile's 64 tree keys, one word per query row of the workgroup
-      if (tid < 64 * NQ) {
-        const int r = row0 + tid;
-        unsigned long long wbits = 0ull;
-        if (r < M) {
-          int a = r % T;
-          int guard = 0;
-          while (a >= 0 && guard++ <= CASCADE_MAX_TREE) {
-            const int rel = a - kbase;
-            if (rel < 0) break;   // ancestors only get smaller
-            if (rel < 64) wbits |= 1ull << rel;
-            a = sm.parent[a];
-          }
-        }
-        sm.anc[tid] = wbits;
-      }
-    }
-    __syncthreads();
+    // tile t+1 (requested one iteration ago) goes to the other buffer, tile t+2 is requested
+    store_tile(t + 1, buf ^ 1);
+    request_tile(t + 2);
 
     // S^T = K Q^T : st[n][kt] holds keys 16*kt + 4*g + c for query l16
     f32x4 st[NQ][4];
@@ -288,7 +294,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         Frag8 kf;
-        kf.u = *(const uint4*)(&sm.k[(16 * kt + l16) * SM::KP + 32 * ks + 8 * g]);
+        kf.u = *(const uint4*)(&tl.k[(16 * kt + l16) * TS::KP + 32 * ks + 8 * g]);
 #pragma unroll
         for (int n = 0; n < NQ; ++n)
           st[n][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[n][ks].v, st[n][kt], 0, 0, 0);
@@ -301,28 +307,37 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
     for (int n = 0; n < NQ; ++n) {
       unsigned long long valid;
       if (tree_tile) {
-        valid = sm.anc[16 * (wave + 4 * n) + l16];
+        valid = s_anc[buf * 256 + 16 * (wave + 4 * n) + l16];
       } else {
         const int rem = klimit - kbase;
         valid = rem >= 64 ? ~0ull : ((1ull << rem) - 1ull);
       }
-      if (q_node[n] < 0) valid = 0ull;
+      if (out_row[n] < 0) valid = 0ull;
       float mx = -INFINITY;
+      if (__ballot(valid != ~0ull) == 0ull) {
+        // every key of the tile is visible to every query of the block: no masking
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
+        for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int kk = 16 * kt + 4 * g + c;
-          float z = st[n][kt][c] * p.scale_log2e;
-          z = ((valid >> kk) & 1ull) ? z : -INFINITY;
-          st[n][kt][c] = z;
-          mx = fmaxf(mx, z);
+          for (int c = 0; c < 4; ++c) {
+            st[n][kt][c] *= p.scale_log2e;
+            mx = fmaxf(mx, st[n][kt][c]);
+          }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+          const uint32_t nib = (uint32_t)(valid >> (16 * kt + 4 * g));   // this lane's 4 keys of sub-tile kt
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const float z = ((nib >> c) & 1u) ? st[n][kt][c] * p.scale_log2e : -INFINITY;
+            st[n][kt][c] = z;
+            mx = fmaxf(mx, z);
+          }
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      }
+      mx = rows4_max(mx);
       const float m_new = fmaxf(m_run[n], mx);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = fast_exp2(m_run[n] - m_use);   // -inf - finite = -inf -> 0
       float ls = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
@@ -332,10 +347,15 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
           st[n][kt][c] = e;
           ls += e;
         }
-      l_run[n] = l_run[n] * alpha + ls;
-      m_run[n] = m_new;
+      if (__ballot(m_new != m_run[n]) != 0ull) {
+        // the running maximum moved for some query of the block: rescale the accumulators
+        const float alpha = fast_exp2(m_run[n] - m_use);   // -inf - finite = -inf -> 0
+        l_run[n] *= alpha;
 #pragma unroll
-      for (int db = 0; db < DB; ++db) ot[n][db] *= alpha;
+        for (int db = 0; db < DB; ++db) ot[n][db] *= alpha;
+        m_run[n] = m_new;
+      }
+      l_run[n] += ls;
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         pf[n][j].u.x = pack_bf16x2(st[n][2 * j][0], st[n][2 * j][1]);
@@ -345,28 +365,29 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
       }
     }
 
-    // O^T += V^T P^T : A operand rows = d, k slots = keys {32j+4g+0..3, 32j+16+4g+0..3}
+    // O^T += V^T P^T.  Operand slots of lane (l16, g): keys 32j + 4g + {0..3} and 32j + 16 + 4g + {0..3}
+    // at d = 16 db + l16, fetched by two transposing loads from the row-major V tile.
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        Frag8 vf;
-        const uint16_t* vp = &sm.vt[(16 * db + l16) * SM::VP + 32 * j + 4 * g];
-        vf.h[0] = *(const uint2*)(vp);
-        vf.h[1] = *(const uint2*)(vp + 16);
+        const uint16_t* vp = &tl.v[(32 * j + 4 * g + (l16 >> 2)) * TS::VP + 16 * db + 4 * (l16 & 3)];
+        union { Frag8 f; s16x4 h[2]; } vf;
+        vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp));
+        vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp + 16 * TS::VP));
 #pragma unroll
         for (int n = 0; n < NQ; ++n)
-          ot[n][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[n][j].v, ot[n][db], 0, 0, 0);
+          ot[n][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.f.v, pf[n][j].v, ot[n][db], 0, 0, 0);
       }
     }
+    __syncthreads();   // tile t consumed by every wave; tile t+1 complete in the other buffer
   }
 
   // epilogue: lane (query l16, g) owns d = 16*db + 4*g + c
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
     float l = l_run[n];
-    l += __shfl_xor(l, 16, WAVE);
-    l += __shfl_xor(l, 32, WAVE);
+    l = rows4_sum(l);
     if (out_row[n] < 0) continue;
     if (SPLIT) {
       float* wo = p.ws_o + ((int64_t)split * p.n_rows_total + out_row[n]) * D;
@@ -402,7 +423,6 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
 // each group of 16 lanes, lane i passes the address of 4 consecutive d of key (i / 4), and lane L
 // receives the 4 keys at d + L.  The key groups' (m, l, O) are merged through LDS at the
 // end, so a drafted tree against a short prefix needs neither workspace traffic nor a second kernel.
-typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 template <int D>
 struct KsplitGroupSmem {
@@ -573,8 +593,7 @@ __global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams 
         }
       }
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+    mx = rows4_max(mx);
     const float m_new = fmaxf(m_run, mx);
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = fast_exp2(m_run - m_use);
@@ -615,8 +634,7 @@ __global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams 
   }
 
   // merge the four key groups through LDS (the tile buffers are reused)
-  l_run += __shfl_xor(l_run, 16, WAVE);
-  l_run += __shfl_xor(l_run, 32, WAVE);
+  l_run = rows4_sum(l_run);
   __syncthreads();
   float* mo = (float*)smem_raw;                 // [NKG][64 rows][OP]
   float* mml = mo + NKG * 64 * OP;              // [NKG][64 rows][2]
@@ -741,16 +759,24 @@ AttnParams make_params(cascade_ctx* ctx, const tree_attn_args* a) {
 template <int D, int NQ>
 hipError_t launch_bf16_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
   hipStream_t st = ctx->stream;
+  const size_t smem = 2 * sizeof(TileSmem<D>) + CASCADE_MAX_TREE * sizeof(int) + 2 * 256 * sizeof(unsigned long long);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_kernel<D, NQ, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_bf16_kernel<D, NQ, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
   if (p.n_split > 1) {
     {
       KernelTimer t(ctx, CASCADE_K_ATTN);
-      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, true>), grid, dim3(256), 0, st, p);
+      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, true>), grid, dim3(256), smem, st, p);
     }
     KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
     hipLaunchKernelGGL((attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
   } else {
     KernelTimer t(ctx, CASCADE_K_ATTN);
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, false>), grid, dim3(256), 0, st, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, false>), grid, dim3(256), smem, st, p);
   }
   return hipGetLastError();
 }
@@ -820,7 +846,9 @@ hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a) {
   const int NQ = M <= 64 ? 1 : (M <= 128 ? 2 : 4);
   p.n_sb = (M + 64 * NQ - 1) / (64 * NQ);
   const long base_wgs = (long)a->n_rows * a->n_kv_heads * p.n_sb;
-  int n_split = (int)((512 + base_wgs - 1) / base_wgs);
+  // one workgroup per CU is resident with NQ = 4 (registers), two otherwise: split only to fill those slots
+  const long slots = NQ == 4 ? 256 : 512;
+  int n_split = (int)(slots / base_wgs);
   if (n_split > n_tiles) n_split = n_tiles;
   if (n_split > 16) n_split = 16;
   if (n_split > 1 && per_split * n_split > ctx->attn_ws_bytes) n_split = (int)(ctx->attn_ws_bytes / per_split);

@@ -124,6 +124,24 @@ __device__ __forceinline__ int wave_max_i(int v) {
   return __builtin_amdgcn_readlane(v, 63);
 }
 
+// Reductions across the four 16-lane rows of a wave (lanes l, l^16, l^32, l^48) with the gfx950
+// row-swap instructions: v_permlane16_swap exchanges odd rows of its first operand with even rows
+// of its second, v_permlane32_swap the upper half of the first with the lower half of the second.
+// With both operands equal, the two results hold v[l] and v[l ^ 16] (resp. v[l ^ 32]) in every lane.
+typedef unsigned cascade_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float rows4_max(float v) {
+  cascade_u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a.x), __uint_as_float(a.y));
+  cascade_u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
+}
+__device__ __forceinline__ float rows4_sum(float v) {
+  cascade_u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a.x) + __uint_as_float(a.y);
+  cascade_u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b.x) + __uint_as_float(b.y);
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 // round-to-nearest-even float -> bf16 bits (NaN kept quiet)
