@@ -106,6 +106,16 @@ typedef enum {
 int cascade_set_kernel_timing(cascade_ctx* ctx, int enable);
 int cascade_read_kernel_timing(cascade_ctx* ctx, int kernel_id, double* total_ms, int32_t* launches);
 
+/* Measurement aids for roofline reports (not part of the method): what this device sustains.
+ * Both calls run a small kernel of their own on the ctx stream, wait for it, and return HOST
+ * numbers.  cascade_measure_hbm_read streams `bytes` (>= 16, buf 16-byte aligned, DEVICE, only
+ * read) `repeats` (1..1000) times with plain coalesced 16-byte loads and returns 1e9 bytes per
+ * second; give it a buffer larger than the 256 MB last-level cache to measure HBM.
+ * cascade_measure_mfma_bf16 runs `iters` (1..2^20) rounds of eight independent 32x32x16 bf16 MFMA
+ * chains per wave, operands in registers, on 32 waves per compute unit, and returns 1e12 flop/s. */
+int cascade_measure_hbm_read(cascade_ctx* ctx, const void* buf, int64_t bytes, int32_t repeats, double* gb_per_s);
+int cascade_measure_mfma_bf16(cascade_ctx* ctx, int32_t iters, double* tflop_per_s);
+
 /* ---------------------------------------------------------------------------------------------
  * tree_verify_attn — the target model's parallel pass over the drafted tree, one decoder layer's
  * attention (Preliminaries: the target evaluates all draft tokens in one parallel forward pass,

@@ -23,7 +23,8 @@ W_ROWMAJOR, W_PACKED32 = 0, 1
 OK, EINVAL, ESHAPE, EDTYPE, ENOMEM, EHIP, ETREE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["cascade_create", "cascade_destroy", "cascade_strerror", "cascade_device_status", "cascade_workspace_bytes",
-           "cascade_set_kernel_timing", "cascade_read_kernel_timing", "cascade_pack_lmhead_w", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path"]
+           "cascade_set_kernel_timing", "cascade_read_kernel_timing", "cascade_measure_hbm_read",
+           "cascade_measure_mfma_bf16", "cascade_pack_lmhead_w", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path"]
 
 _vp, _i32, _i64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
 
@@ -88,6 +89,10 @@ def load_library() -> C.CDLL:
     lib.cascade_set_kernel_timing.restype = C.c_int
     lib.cascade_read_kernel_timing.argtypes = [_vp, C.c_int, C.POINTER(C.c_double), C.POINTER(_i32)]
     lib.cascade_read_kernel_timing.restype = C.c_int
+    lib.cascade_measure_hbm_read.argtypes = [_vp, _vp, _i64, _i32, C.POINTER(C.c_double)]
+    lib.cascade_measure_hbm_read.restype = C.c_int
+    lib.cascade_measure_mfma_bf16.argtypes = [_vp, _i32, C.POINTER(C.c_double)]
+    lib.cascade_measure_mfma_bf16.restype = C.c_int
     lib.cascade_pack_lmhead_w.argtypes = [_vp, _vp, _i32, _i32, _vp]
     lib.cascade_pack_lmhead_w.restype = C.c_int
     for name, st in (("tree_verify_attn", tree_attn_args), ("lmhead_softmax_cfg", lmhead_args),
@@ -158,6 +163,18 @@ class Context:
         ms, n = C.c_double(), _i32()
         _check(self.lib.cascade_read_kernel_timing(self.handle, kernel_id, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+    def measure_hbm_read(self, buf, repeats: int = 10) -> float:
+        """GB/s this device sustains for a plain streaming read of the tensor `buf`."""
+        out = C.c_double()
+        _check(self.lib.cascade_measure_hbm_read(self.handle, _ptr(buf), buf.numel() * buf.element_size(), repeats, C.byref(out)))
+        return out.value
+
+    def measure_mfma_bf16(self, iters: int = 4096) -> float:
+        """TFLOP/s of a register-only bf16 MFMA loop on this device."""
+        out = C.c_double()
+        _check(self.lib.cascade_measure_mfma_bf16(self.handle, iters, C.byref(out)))
+        return out.value
 
 
 def tree_verify_attn(ctx: Context, *, node_off, parent, prefix_len, q, k_tree, v_tree, k_cache, v_cache, out,
