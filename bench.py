@@ -84,6 +84,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--row-major-w", action="store_true", help="keep the LM-head matrix row-major (default: packed once, as at model load)")
     ap.add_argument("--cache-warm", action="store_true", help="also time the steps on one copy of the inputs (served from the last-level cache)")
+    ap.add_argument("--commit-layers", type=int, default=30, help="decoder layers in the separately timed KV commit (0: skip)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -156,6 +157,33 @@ def main() -> int:
             kernel_us[name] = ms * 1e3 / n
     ds.ctx.set_kernel_timing(False)
 
+    # the KV commit that follows the step (not part of the step metric): all decoder layers' worth of
+    # tree keys / values, the path the step just chose, appended to a cache with room
+    commit = None
+    if args.commit_layers > 0:
+        Lc, S, Hkv, D = args.commit_layers, inp.n_rows, inp.n_kv_heads, inp.head_dim
+        cap = inp.prefix_cap + inp.max_depth + 4
+        dt = ds.k_tree.dtype
+        kt = torch.randn((Lc, ds.k_tree.shape[0], Hkv, D), device="cuda").to(dt)
+        vt = torch.randn((Lc, ds.k_tree.shape[0], Hkv, D), device="cuda").to(dt)
+        kc = torch.zeros((Lc, S, Hkv, cap, D), dtype=dt, device="cuda")
+        vc = torch.zeros((Lc, S, Hkv, cap, D), dtype=dt, device="cuda")
+        row_prompt = (torch.arange(S, device="cuda", dtype=torch.int32) // (2 if inp.cfg else 1)).to(torch.int32)
+        plen_out = torch.empty_like(ds.prefix_len)
+        ds.ctx.set_kernel_timing(True)
+        for i in range(60):
+            binding.kv_commit(ds.ctx, node_off=ds.row_node_off, row_prompt=row_prompt, accept_len=ds.accept_len,
+                              path_nodes=ds.path_nodes, k_tree=kt, v_tree=vt, k_cache=kc, v_cache=vc,
+                              prefix_len=ds.prefix_len, prefix_len_out=plen_out)
+            if i == 9:
+                ds.ctx.read_kernel_timing(6)      # drop the warm-up launches
+        ms, n = ds.ctx.read_kernel_timing(6)
+        ds.ctx.set_kernel_timing(False)
+        assert ds.ctx.device_status() == binding.OK
+        moved = int((plen_out - ds.prefix_len).sum().item()) * Lc * Hkv * D * kt.element_size() * 2 * 2   # K and V, read + write
+        commit = {"layers": Lc, "us": ms * 1e3 / n, "bytes": moved, "GBs": moved / (ms * 1e-3 / n) / 1e9}
+        del kt, vt, kc, vc
+
     # what this device sustains: a plain streaming read of 1 GiB and a register-only MFMA loop
     big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     big.zero_()
@@ -206,6 +234,7 @@ def main() -> int:
         "attn_hbm_frac": (algorithmic_bytes_attn(inp) / ((kernel_us.get("attn", 0) + kernel_us.get("attn_merge", 0)) * 1e-6) / 1e9
                           / HBM_PEAK_GBS) if kernel_us.get("attn") else None,
         "accept_len": ds.accept_len.cpu().tolist(),
+        "kv_commit": commit,
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

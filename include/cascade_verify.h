@@ -9,6 +9,9 @@
  *   cascade_accept      per-node quantities of the relaxed acceptance rule (Eq. 1, Eq. 2, Eq. 3)
  *   select_path         the walk of Alg. 2 (budget, acceptance test) and the correction step of Alg. 1
  *
+ * and, between two steps, kv_commit appends the keys / values of the tokens that were kept to the
+ * prefix cache.
+ *
  * General conventions
  * -------------------
  *  - C99, no C++ types.  Every pointer inside an args struct is a DEVICE pointer unless its
@@ -84,7 +87,8 @@ int cascade_destroy(cascade_ctx* ctx);
 const char* cascade_strerror(int status);
 /* Synchronises the ctx stream, returns CASCADE_OK or CASCADE_ETREE if any kernel since the last
  * call met a violated precondition (parent[i] >= i, more than CASCADE_MAX_WIDTH children, token
- * outside [0, vocab), tree deeper than max_depth), and clears the flag. */
+ * outside [0, vocab), tree deeper than max_depth, a kv_commit row without room or with a path entry
+ * outside its tree), and clears the flag. */
 int cascade_device_status(cascade_ctx* ctx);
 /* Bytes of device workspace the ctx holds (HOST query). */
 int64_t cascade_workspace_bytes(const cascade_ctx* ctx);
@@ -101,7 +105,8 @@ typedef enum {
   CASCADE_K_ROW_STATS = 3,   /* row max / top-k threshold / log-sum-exp */
   CASCADE_K_ACCEPT = 4,
   CASCADE_K_SELECT = 5,
-  CASCADE_K_COUNT = 6
+  CASCADE_K_COMMIT = 6,      /* kv_commit */
+  CASCADE_K_COUNT = 7
 } cascade_kernel_id;
 int cascade_set_kernel_timing(cascade_ctx* ctx, int enable);
 int cascade_read_kernel_timing(cascade_ctx* ctx, int kernel_id, double* total_ms, int32_t* launches);
@@ -261,6 +266,47 @@ typedef struct {
   float* tvd_used;
 } select_args;
 int select_path(cascade_ctx* ctx, const select_args* args);
+
+/* ---------------------------------------------------------------------------------------------
+ * kv_commit — after select_path: the tokens that are now part of the sequence get their keys and
+ * values appended to the prefix cache, for every decoder layer (Preliminaries: accepted tokens are
+ * appended to the prefix; iterative tree decoding forms the whole image sequence).  The root of a
+ * tree is the token the previous step emitted last; its key / value were produced in this step, so
+ * it goes first, then the accepted nodes in path order.  The last emitted token (correction or
+ * bonus) has no key / value yet: it is the next tree's root.
+ *
+ * For row s with prompt b = row_prompt[s], P = prefix_len[s], n = accept_len[b]:
+ *     node_0 = 0,  node_j = path_nodes[b, j-1]                       (j = 1 .. n)
+ *     cache[layer, s, kvh, P + j, :] = tree[layer, node_off[s] + node_j, kvh, :]   for K and V
+ *     prefix_len_out[s] = P + 1 + n
+ * A row with P + 1 + n > prefix_cap is left untouched (prefix_len_out[s] = P) and a path entry
+ * outside the row's tree is skipped; both set the flag cascade_device_status reports.
+ * Pure copy: values are moved bit for bit.
+ *
+ *     k_tree, v_tree   [n_layers, N, n_kv_heads, head_dim] dtype, contiguous (N = node_off[n_rows])
+ *     k_cache, v_cache element (layer, s, kvh, pos, d) at layer*cache_stride_layer +
+ *                      s*cache_stride_row + kvh*cache_stride_head + pos*cache_stride_pos + d
+ *                      (strides in ELEMENTS; head_dim and all strides multiples of 16 bytes)
+ *     prefix_len_out   must not alias prefix_len
+ */
+typedef struct {
+  int32_t n_rows, n_prompts;
+  const int32_t* node_off;      /* [n_rows+1] DEVICE, row packing as in tree_verify_attn */
+  const int32_t* row_prompt;    /* [n_rows] DEVICE (guidance rows of a prompt share its path) */
+  const int32_t* accept_len;    /* [n_prompts] DEVICE, as written by select_path */
+  const int32_t* path_nodes;    /* [n_prompts, max_depth] DEVICE, as written by select_path */
+  int32_t max_depth;
+  int32_t n_nodes_total;        /* HOST copy of node_off[n_rows] */
+  cascade_dtype dtype;
+  int32_t n_layers, n_kv_heads, head_dim;
+  const void *k_tree, *v_tree;
+  void *k_cache, *v_cache;
+  int64_t cache_stride_layer, cache_stride_row, cache_stride_head, cache_stride_pos;
+  int32_t prefix_cap;           /* positions allocated per (layer, row, kv head) */
+  const int32_t* prefix_len;    /* [n_rows] DEVICE */
+  int32_t* prefix_len_out;      /* [n_rows] DEVICE */
+} kv_commit_args;
+int kv_commit(cascade_ctx* ctx, const kv_commit_args* args);
 
 #ifdef __cplusplus
 }

@@ -24,7 +24,7 @@ OK, EINVAL, ESHAPE, EDTYPE, ENOMEM, EHIP, ETREE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["cascade_create", "cascade_destroy", "cascade_strerror", "cascade_device_status", "cascade_workspace_bytes",
            "cascade_set_kernel_timing", "cascade_read_kernel_timing", "cascade_measure_hbm_read",
-           "cascade_measure_mfma_bf16", "cascade_pack_lmhead_w", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path"]
+           "cascade_measure_mfma_bf16", "cascade_pack_lmhead_w", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path", "kv_commit"]
 
 _vp, _i32, _i64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
 
@@ -63,6 +63,14 @@ class select_args(C.Structure):
                 ("emitted", _vp), ("terminal", _vp), ("tvd_used", _vp)]
 
 
+class kv_commit_args(C.Structure):
+    _fields_ = [("n_rows", _i32), ("n_prompts", _i32), ("node_off", _vp), ("row_prompt", _vp), ("accept_len", _vp),
+                ("path_nodes", _vp), ("max_depth", _i32), ("n_nodes_total", _i32), ("dtype", C.c_int), ("n_layers", _i32),
+                ("n_kv_heads", _i32), ("head_dim", _i32), ("k_tree", _vp), ("v_tree", _vp), ("k_cache", _vp), ("v_cache", _vp),
+                ("cache_stride_layer", _i64), ("cache_stride_row", _i64), ("cache_stride_head", _i64),
+                ("cache_stride_pos", _i64), ("prefix_cap", _i32), ("prefix_len", _vp), ("prefix_len_out", _vp)]
+
+
 _lib = None
 
 
@@ -96,7 +104,7 @@ def load_library() -> C.CDLL:
     lib.cascade_pack_lmhead_w.argtypes = [_vp, _vp, _i32, _i32, _vp]
     lib.cascade_pack_lmhead_w.restype = C.c_int
     for name, st in (("tree_verify_attn", tree_attn_args), ("lmhead_softmax_cfg", lmhead_args),
-                     ("cascade_accept", accept_args), ("select_path", select_args)):
+                     ("cascade_accept", accept_args), ("select_path", select_args), ("kv_commit", kv_commit_args)):
         fn = getattr(lib, name)
         fn.argtypes = [_vp, C.POINTER(st)]
         fn.restype = C.c_int
@@ -241,6 +249,25 @@ def select_path(ctx: Context, *, node_off, parent, token, q_tok, m_int, m_conv, 
     a.accept_len, a.path_nodes, a.emitted = _ptr(accept_len), _ptr(path_nodes), _ptr(emitted)
     a.terminal, a.tvd_used = _ptr(terminal), _ptr(tvd_used)
     _check(ctx.lib.select_path(ctx.handle, C.byref(a)))
+
+
+def kv_commit(ctx: Context, *, node_off, row_prompt, accept_len, path_nodes, k_tree, v_tree, k_cache, v_cache,
+              prefix_len, prefix_len_out, n_prompts: Optional[int] = None) -> None:
+    """k_tree/v_tree [L,N,Hkv,D]; k_cache/v_cache [L,S,Hkv,cap,D] (last dim contiguous); path_nodes [B,max_depth]."""
+    a = kv_commit_args()
+    a.n_rows, a.n_prompts = prefix_len.numel(), accept_len.numel() if n_prompts is None else n_prompts
+    a.node_off, a.row_prompt, a.accept_len, a.path_nodes = _ptr(node_off), _ptr(row_prompt), _ptr(accept_len), _ptr(path_nodes)
+    a.max_depth = path_nodes.shape[1] if path_nodes is not None else 0
+    a.n_nodes_total = k_tree.shape[1]
+    a.dtype = _dtype_code(k_tree)
+    a.n_layers, a.n_kv_heads, a.head_dim = k_tree.shape[0], k_tree.shape[2], k_tree.shape[3]
+    assert k_tree.is_contiguous() and v_tree.is_contiguous()
+    assert k_cache.stride() == v_cache.stride() and k_cache.stride(4) == 1
+    a.k_tree, a.v_tree, a.k_cache, a.v_cache = _ptr(k_tree), _ptr(v_tree), _ptr(k_cache), _ptr(v_cache)
+    a.cache_stride_layer, a.cache_stride_row, a.cache_stride_head, a.cache_stride_pos = k_cache.stride()[:4]
+    a.prefix_cap = k_cache.shape[3]
+    a.prefix_len, a.prefix_len_out = _ptr(prefix_len), _ptr(prefix_len_out)
+    _check(ctx.lib.kv_commit(ctx.handle, C.byref(a)))
 
 
 # ------------------------------------------------------------------------------------------------

@@ -241,4 +241,29 @@ int select_path(cascade_ctx* ctx, const select_args* a) {
   return e == hipSuccess ? CASCADE_OK : hip_fail(e);
 }
 
+int kv_commit(cascade_ctx* ctx, const kv_commit_args* a) {
+  if (!ctx || !a) return CASCADE_EINVAL;
+  if (!a->node_off || !a->row_prompt || !a->accept_len || !a->k_tree || !a->v_tree || !a->k_cache || !a->v_cache ||
+      !a->prefix_len || !a->prefix_len_out || a->prefix_len == a->prefix_len_out)
+    return CASCADE_EINVAL;
+  if (a->dtype != CASCADE_F32 && a->dtype != CASCADE_BF16) return CASCADE_EDTYPE;
+  if (a->n_rows < 0 || a->n_prompts < 0 || a->n_nodes_total < 0 || a->max_depth < 0 || a->n_layers < 0 || a->n_kv_heads <= 0 ||
+      a->head_dim <= 0 || a->prefix_cap < 0)
+    return CASCADE_EINVAL;
+  if (a->max_depth > 0 && !a->path_nodes) return CASCADE_EINVAL;
+  const int64_t e = a->dtype == CASCADE_BF16 ? 2 : 4;
+  const int64_t strides[4] = {a->cache_stride_layer, a->cache_stride_row, a->cache_stride_head, a->cache_stride_pos};
+  for (int i = 0; i < 4; ++i)
+    if (strides[i] < 0 || (strides[i] * e) % 16) return CASCADE_ESHAPE;
+  if ((a->head_dim * e) % 16 || a->cache_stride_pos < a->head_dim) return CASCADE_ESHAPE;
+  if (((uintptr_t)a->k_tree | (uintptr_t)a->v_tree | (uintptr_t)a->k_cache | (uintptr_t)a->v_cache) & 15) return CASCADE_EINVAL;
+  const cascade_limits& L = ctx->lim;
+  if (a->n_rows > L.max_rows || a->n_nodes_total > L.max_nodes_total || a->max_depth > CASCADE_MAX_DEPTH) return CASCADE_ESHAPE;
+  if ((int64_t)a->n_rows * (a->max_depth + 1) > 0x7fffffff || a->n_layers > 65535) return CASCADE_ESHAPE;
+  if (a->n_rows == 0 || a->n_layers == 0) return CASCADE_OK;
+  if (a->n_prompts == 0) return CASCADE_EINVAL;
+  hipError_t err = launch_kv_commit(ctx, a);
+  return err == hipSuccess ? CASCADE_OK : hip_fail(err);
+}
+
 }  // extern "C"

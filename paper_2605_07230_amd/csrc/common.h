@@ -48,7 +48,9 @@ enum {
   CASCADE_FLAG_PARENT = 1,   // parent[i] >= i or < -1, or a second root
   CASCADE_FLAG_WIDTH = 2,    // more than CASCADE_MAX_WIDTH children
   CASCADE_FLAG_TOKEN = 4,    // token outside [0, vocab)
-  CASCADE_FLAG_DEPTH = 8     // path longer than max_depth
+  CASCADE_FLAG_DEPTH = 8,    // path longer than max_depth
+  CASCADE_FLAG_CAPACITY = 16, // kv_commit: a row's cache has no room for root + accepted path
+  CASCADE_FLAG_PATH = 32     // kv_commit: a path entry outside the row's tree, or a bad row_prompt
 };
 
 // launchers (one translation unit each); all return hipError_t of the launch
@@ -60,6 +62,7 @@ hipError_t launch_row_stats(cascade_ctx* ctx, const lmhead_args* a);
 hipError_t launch_pack_w(cascade_ctx* ctx, const void* w, int vocab, int hidden, void* w_packed);
 hipError_t launch_accept(cascade_ctx* ctx, const accept_args* a);
 hipError_t launch_select(cascade_ctx* ctx, const select_args* a);
+hipError_t launch_kv_commit(cascade_ctx* ctx, const kv_commit_args* a);
 
 // ----------------------------------------------------------------------------------------------
 // device helpers

@@ -378,3 +378,69 @@ def make_config(index: int, seed: int = 0, **overrides) -> VerifyInputs:
         raise ValueError("config index must be 0..4")
     kw.update(overrides)
     return make_inputs(seed=seed, **kw)
+
+
+# ------------------------------------------------------------------------------------------------
+# inputs of the KV commit that follows a step
+
+@dataclasses.dataclass
+class CommitInputs:
+    """Multi-layer tree keys / values and a prefix cache with room to append (host arrays)."""
+
+    n_layers: int
+    k_tree: np.ndarray        # [L, N_a, Hkv, D]
+    v_tree: np.ndarray
+    k_cache: np.ndarray       # [L, S, Hkv, cap, D]
+    v_cache: np.ndarray
+    prefix_cap: int
+    row_prompt: np.ndarray    # [S] int32
+    accept_len: np.ndarray    # [B] int32     a seeded root-to-node walk per prompt
+    path_nodes: np.ndarray    # [B, max_depth] int32, -1 padded
+
+
+def random_paths(inp: VerifyInputs, seed: int = 0):
+    """For every prompt a seeded walk from the root: at each node stop w.p. 0.25, else descend to a
+    random child.  Tree structure only; stands in for what the path selection would return."""
+    rng = np.random.default_rng(seed + 4242)
+    B, md = inp.n_prompts, max(inp.max_depth, 1)
+    accept_len = np.zeros(B, dtype=np.int32)
+    path_nodes = -np.ones((B, md), dtype=np.int32)
+    for b in range(B):
+        par = inp.parent[inp.node_off[b]:inp.node_off[b + 1]]
+        cur, n = 0, 0
+        while True:
+            kids = np.nonzero(par == cur)[0]
+            if len(kids) == 0 or rng.random() < 0.25:
+                break
+            cur = int(kids[int(rng.integers(0, len(kids)))])
+            path_nodes[b, n] = cur
+            n += 1
+        accept_len[b] = n
+    return accept_len, path_nodes
+
+
+def make_commit_inputs(inp: VerifyInputs, n_layers: int, seed: int = 0, slack: int = 3) -> CommitInputs:
+    """Layer 0 reuses the step's own tree keys / values and cache contents; further layers are fresh
+    N(0,1) draws.  The cache gets max_depth + 1 + slack positions beyond the longest prefix."""
+    rng = np.random.default_rng(seed + 977)
+    rnd = round_bf16 if inp.dtype == "bf16" else (lambda x: x)
+    S, Hkv, D = inp.n_rows, inp.n_kv_heads, inp.head_dim
+    N_a = inp.q.shape[0]
+    cap = inp.prefix_cap + inp.max_depth + 1 + slack
+    k_tree = np.empty((n_layers, N_a, Hkv, D), dtype=np.float32)
+    v_tree = np.empty_like(k_tree)
+    k_cache = np.zeros((n_layers, S, Hkv, cap, D), dtype=np.float32)
+    v_cache = np.zeros_like(k_cache)
+    for layer in range(n_layers):
+        if layer == 0:
+            k_tree[0], v_tree[0] = inp.k_tree, inp.v_tree
+            k_cache[0, :, :, :inp.prefix_cap], v_cache[0, :, :, :inp.prefix_cap] = inp.k_cache, inp.v_cache
+        else:
+            k_tree[layer], v_tree[layer] = rnd(_randn(rng, (N_a, Hkv, D))), rnd(_randn(rng, (N_a, Hkv, D)))
+            k_cache[layer, :, :, :inp.prefix_cap] = rnd(_randn(rng, (S, Hkv, inp.prefix_cap, D)))
+            v_cache[layer, :, :, :inp.prefix_cap] = rnd(_randn(rng, (S, Hkv, inp.prefix_cap, D)))
+    rows_per_prompt = 2 if inp.cfg else 1
+    row_prompt = (np.arange(S) // rows_per_prompt).astype(np.int32)
+    accept_len, path_nodes = random_paths(inp, seed)
+    return CommitInputs(n_layers=n_layers, k_tree=k_tree, v_tree=v_tree, k_cache=k_cache, v_cache=v_cache, prefix_cap=cap,
+                        row_prompt=row_prompt, accept_len=accept_len, path_nodes=path_nodes)

@@ -1,0 +1,153 @@
+"""kv_commit on the GPU against the CPU checker: a pure copy, compared bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import commit_oracle as co
+from paper_2605_07230_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(inp, ci, accept_len=None, path_nodes=None, prefix_len=None, cap_limit=None):
+    from paper_2605_07230_amd import binding
+    dev = torch.device("cuda:0")
+    dt = torch.bfloat16 if inp.dtype == "bf16" else torch.float32
+    accept_len = ci.accept_len if accept_len is None else accept_len
+    path_nodes = ci.path_nodes if path_nodes is None else path_nodes
+    prefix_len = inp.prefix_len if prefix_len is None else prefix_len
+    k_cache_h, v_cache_h = ci.k_cache, ci.v_cache
+    if cap_limit is not None:
+        k_cache_h, v_cache_h = k_cache_h[:, :, :, :cap_limit].copy(), v_cache_h[:, :, :, :cap_limit].copy()
+    cap = k_cache_h.shape[3]
+    up = lambda x, d=None: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(d) if d else torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    k_tree, v_tree = up(ci.k_tree, dt), up(ci.v_tree, dt)
+    k_cache, v_cache = up(k_cache_h, dt), up(v_cache_h, dt)
+    plen, plen_out = up(prefix_len), torch.full((inp.n_rows,), -7, dtype=torch.int32, device=dev)
+    ctx = binding.Context(max_rows=inp.n_rows, max_nodes_total=ci.k_tree.shape[1], max_nodes_per_tree=min(1024, ci.k_tree.shape[1]),
+                          max_prefix=cap, n_heads=inp.n_heads, head_dim=inp.head_dim, hidden=inp.hidden, vocab=inp.vocab)
+    binding.kv_commit(ctx, node_off=up(inp.row_node_off), row_prompt=up(ci.row_prompt), accept_len=up(accept_len),
+                      path_nodes=up(path_nodes), k_tree=k_tree, v_tree=v_tree, k_cache=k_cache, v_cache=v_cache,
+                      prefix_len=plen, prefix_len_out=plen_out)
+    status = ctx.device_status()
+    ek, ev, elen, ovf = co.kv_commit(ci.k_tree, ci.v_tree, k_cache_h, v_cache_h, inp.row_node_off, ci.row_prompt,
+                                     prefix_len, cap, accept_len, path_nodes)
+    return (k_cache.float().cpu().numpy(), v_cache.float().cpu().numpy(), plen_out.cpu().numpy(), status), (ek, ev, elen, ovf)
+
+
+@pytest.mark.parametrize("config,layers", [(0, 3), (1, 2), (3, 2)])
+def test_commit_matches_checker(config, layers):
+    from paper_2605_07230_amd import binding
+    inp = wl.make_config(config, 0)
+    ci = wl.make_commit_inputs(inp, layers, seed=1)
+    (gk, gv, glen, status), (ek, ev, elen, ovf) = _run(inp, ci)
+    assert status == binding.OK and not ovf.any()
+    np.testing.assert_array_equal(glen, elen)
+    np.testing.assert_array_equal(gk, ek)
+    np.testing.assert_array_equal(gv, ev)
+    assert (glen - inp.prefix_len == 1 + ci.accept_len[ci.row_prompt]).all()
+
+
+def test_commit_deepest_chain_and_zero_length():
+    """Every prompt once with its forced deepest chain, once with nothing accepted."""
+    from paper_2605_07230_amd import binding
+    inp = wl.make_config(3, 2)
+    ci = wl.make_commit_inputs(inp, 2, seed=3)
+    depth = wl.node_depths
+    B, md = inp.n_prompts, inp.max_depth
+    accept_len = np.zeros(B, np.int32)
+    path = -np.ones((B, md), np.int32)
+    for b in range(0, B, 2):     # even prompts: deepest leaf's chain; odd prompts: nothing accepted
+        par = inp.parent[inp.node_off[b]:inp.node_off[b + 1]]
+        d = depth(par)
+        leaf = int(np.argmax(d))
+        chain = []
+        while leaf > 0:
+            chain.append(leaf)
+            leaf = int(par[leaf])
+        chain = chain[::-1]
+        accept_len[b] = len(chain)
+        path[b, :len(chain)] = chain
+    (gk, gv, glen, status), (ek, ev, elen, ovf) = _run(inp, ci, accept_len, path)
+    assert status == binding.OK
+    np.testing.assert_array_equal(glen, elen)
+    np.testing.assert_array_equal(gk, ek)
+    np.testing.assert_array_equal(gv, ev)
+
+
+def test_commit_row_without_room_is_left_alone_and_flagged():
+    from paper_2605_07230_amd import binding
+    inp = wl.make_config(3, 0)
+    ci = wl.make_commit_inputs(inp, 2, seed=1)
+    cap = int(inp.prefix_len.max())          # the longest row has no room at all
+    (gk, gv, glen, status), (ek, ev, elen, ovf) = _run(inp, ci, cap_limit=cap)
+    assert ovf.any() and not ovf.all()
+    assert status == binding.ETREE
+    np.testing.assert_array_equal(glen, elen)
+    np.testing.assert_array_equal(gk, ek)
+    np.testing.assert_array_equal(gv, ev)
+
+
+def test_commit_bad_path_entry_is_skipped_and_flagged():
+    from paper_2605_07230_amd import binding
+    inp = wl.make_config(0, 0)
+    ci = wl.make_commit_inputs(inp, 2, seed=1)
+    accept_len = np.array([2], np.int32)
+    path = -np.ones((1, max(inp.max_depth, 1)), np.int32)
+    path[0, 0], path[0, 1] = 1, 4096        # second entry is outside the 15-node tree
+    dev = torch.device("cuda:0")
+    up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    k_cache, v_cache = up(ci.k_cache), up(ci.v_cache)
+    before = k_cache.clone()
+    plen_out = torch.zeros(1, dtype=torch.int32, device=dev)
+    ctx = binding.Context(max_rows=1, max_nodes_total=15, max_nodes_per_tree=15, max_prefix=ci.prefix_cap, n_heads=inp.n_heads,
+                          head_dim=inp.head_dim, hidden=inp.hidden, vocab=inp.vocab)
+    binding.kv_commit(ctx, node_off=up(inp.row_node_off), row_prompt=up(ci.row_prompt), accept_len=up(accept_len),
+                      path_nodes=up(path), k_tree=up(ci.k_tree), v_tree=up(ci.v_tree), k_cache=k_cache, v_cache=v_cache,
+                      prefix_len=up(inp.prefix_len), prefix_len_out=plen_out)
+    assert ctx.device_status() == binding.ETREE
+    P = int(inp.prefix_len[0])
+    got = k_cache.cpu().numpy()
+    np.testing.assert_array_equal(got[:, 0, :, P], ci.k_tree[:, 0])      # root
+    np.testing.assert_array_equal(got[:, 0, :, P + 1], ci.k_tree[:, 1])  # first accepted node
+    np.testing.assert_array_equal(got[:, 0, :, P + 2], before.cpu().numpy()[:, 0, :, P + 2])   # skipped slot untouched
+
+
+def test_commit_after_a_real_step_then_next_step_attends_the_longer_prefix():
+    """Whole step on the GPU, commit with the path the GPU chose, then attention of a fresh
+    one-node tree against the grown cache; every piece against the checker."""
+    from oracle import verify_oracle as vo
+    from paper_2605_07230_amd import binding
+    import parity_util as pu
+    inp = wl.make_config(1, 4)
+    ds = binding.DeviceStep(inp)
+    ds.step()
+    assert ds.ctx.device_status() == binding.OK
+    accept_len = ds.accept_len.cpu().numpy()
+    path_nodes = ds.path_nodes.cpu().numpy()
+    ci = wl.make_commit_inputs(inp, 1, seed=4)
+    (gk, gv, glen, status), (ek, ev, elen, ovf) = _run(inp, ci, accept_len, path_nodes)
+    assert status == binding.OK
+    np.testing.assert_array_equal(glen, elen)
+    np.testing.assert_array_equal(gk, ek)
+    np.testing.assert_array_equal(gv, ev)
+    # next step: a lone root per row attends the committed prefix
+    dev = torch.device("cuda:0")
+    S = inp.n_rows
+    rng = np.random.default_rng(9)
+    q1 = wl.round_bf16(rng.standard_normal((S, inp.n_heads, inp.head_dim)).astype(np.float32))
+    k1 = wl.round_bf16(rng.standard_normal((S, inp.n_kv_heads, inp.head_dim)).astype(np.float32))
+    v1 = wl.round_bf16(rng.standard_normal((S, inp.n_kv_heads, inp.head_dim)).astype(np.float32))
+    off1 = np.arange(S + 1, dtype=np.int32)
+    par1 = -np.ones(S, np.int32)
+    up = lambda x, d=None: torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(d) if d else torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    bf = torch.bfloat16
+    out = torch.empty((S, inp.n_heads, inp.head_dim), dtype=bf, device=dev)
+    ctx = binding.Context(max_rows=S, max_nodes_total=S, max_nodes_per_tree=1, max_prefix=int(glen.max()), n_heads=inp.n_heads,
+                          head_dim=inp.head_dim, hidden=inp.hidden, vocab=inp.vocab)
+    binding.tree_verify_attn(ctx, node_off=up(off1), parent=up(par1), prefix_len=up(glen), q=up(q1, bf), k_tree=up(k1, bf),
+                             v_tree=up(v1, bf), k_cache=up(gk[0], bf), v_cache=up(gv[0], bf), out=out, max_nodes_per_tree=1,
+                             max_prefix_len=int(glen.max()))
+    assert ctx.device_status() == binding.OK
+    ref, _ = vo.tree_attention(q1, k1, v1, ek[0], ev[0], par1, off1, elen)
+    assert pu.max_rel_err(out.float().cpu().numpy(), ref) < pu.TOL["bf16"]
