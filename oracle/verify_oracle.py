@@ -237,9 +237,10 @@ class PathResult:
     min_margin: float           # smallest relative margin of any comparison that was taken
 
 
-def _try_node(a, lo, acc: AcceptScalars, draft_prob, u, eps, curr, margins):
-    """Alg. 2 body for one tried node: budget-gated aggregation, then Alg. 1's test.  Returns (accepted, curr)."""
-    q_x = float(acc.q_tok[lo + a])
+def _try_node(a, lo, acc: AcceptScalars, draft_prob, u, eps, curr, margins, q_base=None, p_base=None):
+    """Alg. 2 body for one tried node: budget-gated aggregation, then Alg. 1's test.  Returns (accepted, curr).
+    q_base / p_base replace the node's stored target / drafter probability (residual walk)."""
+    q_x = float(acc.q_tok[lo + a]) if q_base is None else float(q_base)
     if acc.n_int[lo + a] > 0:
         m = float(acc.m_int[lo + a])
         margins.append(abs(curr + m - eps) / max(eps, 1e-30))
@@ -253,6 +254,8 @@ def _try_node(a, lo, acc: AcceptScalars, draft_prob, u, eps, curr, margins):
             q_x += m
             curr += m
     p_x = 1.0 if draft_prob is None else float(draft_prob[lo + a])
+    if p_base is not None:
+        p_x = float(p_base)
     r = float(u[lo + a])
     lhs = r * p_x                       # r < min(1, q_x/p_x)  <=>  r*p_x < q_x   (0 <= r < 1, p_x > 0)
     margins.append(abs(lhs - q_x) / max(abs(lhs), abs(q_x), 1e-30))
