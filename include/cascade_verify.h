@@ -214,7 +214,10 @@ int lmhead_softmax_cfg(cascade_ctx* ctx, const lmhead_args* args);
  *     m_int[a]  = sum of Q[t] over distinct t in tokens(I_a) \ {token[a]}
  *     m_conv[a] = sum of Q[t] over distinct t in tokens(C_a) \ {token[a]} \ tokens(I_a)
  *     cos_parent[a] = cos(F_p, F_a)
- * F = rows of h_cond (the conditional row's final hidden state, the LM-head input).  cos is 0 when
+ * F = rows of h_cond (the conditional row's final hidden state, the LM-head input), or, with
+ * feature_space = CASCADE_FEATURES_LOGITS, the node's row of mixed logits (App. "Preliminary
+ * Findings": cosine similarity of target logits as the alternative measure; h_cond, h_dtype and
+ * hidden are then ignored).  cos is 0 when
  * a norm is 0.  A threshold > 1 disables that relaxation.  Root entries are written as 0.
  * Dot products and norms accumulate in float32.
  *
@@ -222,6 +225,7 @@ int lmhead_softmax_cfg(cascade_ctx* ctx, const lmhead_args* args);
  *     logits [N, vocab] float32 and row_thr/row_lse [N] as written by lmhead_softmax_cfg
  *     outputs [N]: q_tok, m_int, m_conv, cos_parent float32;  n_int, n_conv int32
  */
+typedef enum { CASCADE_FEATURES_HIDDEN = 0, CASCADE_FEATURES_LOGITS = 1 } cascade_feature_space;
 typedef struct {
   cascade_dtype h_dtype;
   int32_t n_prompts, n_nodes_total, hidden, vocab;
@@ -231,6 +235,7 @@ typedef struct {
   float tau_pos, tau_seq;
   float *q_tok, *m_int, *m_conv, *cos_parent;
   int32_t *n_int, *n_conv;
+  cascade_feature_space feature_space;   /* 0 = hidden states */
 } accept_args;
 int cascade_accept(cascade_ctx* ctx, const accept_args* args);
 
@@ -245,6 +250,14 @@ int cascade_accept(cascade_ctx* ctx, const accept_args* args);
  * cur with the tokens of the children rejected at that last level removed: the smallest v with
  * cumulative mass > u_bonus[b] * remaining mass (vocabulary order).
  * All compares and sums in float32.
+ *
+ * Residual walk (draft_dist != NULL; SEQUENTIAL only; vocab a multiple of 4): row a of draft_dist is
+ * the full drafter distribution node a was drawn from.  The level starts with f = the distribution
+ * of cur; the tried child a uses q = f[token[a]] and drafter probability draft_dist[a][token[a]]
+ * (draft_prob is ignored), the relaxation masses unchanged; each rejection replaces f by Alg. 1's
+ * residual norm([f - draft_dist[a]]_+) (f is kept if nothing would be left), so later siblings are
+ * verified against what the earlier ones left over, and the last token is drawn from the final f
+ * (no tokens are removed beyond that).  With one draft per level this is Alg. 1 exactly.
  *
  *     draft_prob [N] float32 (NULL => 1), u [N] float32 in [0,1), u_bonus [n_prompts] in [0,1)
  *     accept_len [n_prompts]; path_nodes [n_prompts, max_depth] local indices, -1 padded;
@@ -264,6 +277,7 @@ typedef struct {
   const float *logits, *row_thr, *row_lse;
   int32_t *accept_len, *path_nodes, *emitted, *terminal;
   float* tvd_used;
+  const float* draft_dist;    /* nullable; [N, vocab] => residual walk (see above) */
 } select_args;
 int select_path(cascade_ctx* ctx, const select_args* args);
 

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libcascade_verify.so")
 
 F32, BF16 = 0, 1
 WALK_SEQUENTIAL, WALK_LONGEST = 0, 1
+FEATURES_HIDDEN, FEATURES_LOGITS = 0, 1
 K_ATTN, K_ATTN_MERGE, K_LMHEAD, K_ROW_STATS, K_ACCEPT, K_SELECT = range(6)
 W_ROWMAJOR, W_PACKED32 = 0, 1
 OK, EINVAL, ESHAPE, EDTYPE, ENOMEM, EHIP, ETREE = 0, -1, -2, -3, -4, -5, -6
@@ -52,7 +53,7 @@ class accept_args(C.Structure):
     _fields_ = [("h_dtype", C.c_int), ("n_prompts", _i32), ("n_nodes_total", _i32), ("hidden", _i32), ("vocab", _i32),
                 ("node_off", _vp), ("parent", _vp), ("token", _vp), ("h_cond", _vp), ("logits", _vp), ("row_thr", _vp),
                 ("row_lse", _vp), ("tau_pos", _f32), ("tau_seq", _f32), ("q_tok", _vp), ("m_int", _vp), ("m_conv", _vp),
-                ("cos_parent", _vp), ("n_int", _vp), ("n_conv", _vp)]
+                ("cos_parent", _vp), ("n_int", _vp), ("n_conv", _vp), ("feature_space", C.c_int)]
 
 
 class select_args(C.Structure):
@@ -60,7 +61,7 @@ class select_args(C.Structure):
                 ("node_off", _vp), ("parent", _vp), ("token", _vp), ("q_tok", _vp), ("m_int", _vp), ("m_conv", _vp),
                 ("n_int", _vp), ("n_conv", _vp), ("draft_prob", _vp), ("u", _vp), ("u_bonus", _vp), ("eps_tvd", _f32),
                 ("logits", _vp), ("row_thr", _vp), ("row_lse", _vp), ("accept_len", _vp), ("path_nodes", _vp),
-                ("emitted", _vp), ("terminal", _vp), ("tvd_used", _vp)]
+                ("emitted", _vp), ("terminal", _vp), ("tvd_used", _vp), ("draft_dist", _vp)]
 
 
 class kv_commit_args(C.Structure):
@@ -226,8 +227,9 @@ def lmhead_softmax_cfg(ctx: Context, *, h_cond, h_uncond, w, cfg_scale, temperat
 
 
 def cascade_accept(ctx: Context, *, node_off, parent, token, h_cond, logits, row_thr, row_lse, tau_pos, tau_seq,
-                   q_tok, m_int, m_conv, cos_parent, n_int, n_conv) -> None:
+                   q_tok, m_int, m_conv, cos_parent, n_int, n_conv, feature_space: int = FEATURES_HIDDEN) -> None:
     a = accept_args()
+    a.feature_space = feature_space
     a.h_dtype = _dtype_code(h_cond)
     a.n_prompts, a.n_nodes_total, a.hidden, a.vocab = node_off.numel() - 1, h_cond.shape[0], h_cond.shape[1], logits.shape[1]
     a.node_off, a.parent, a.token, a.h_cond = _ptr(node_off), _ptr(parent), _ptr(token), _ptr(h_cond)
@@ -239,8 +241,10 @@ def cascade_accept(ctx: Context, *, node_off, parent, token, h_cond, logits, row
 
 
 def select_path(ctx: Context, *, node_off, parent, token, q_tok, m_int, m_conv, n_int, n_conv, draft_prob, u, u_bonus,
-                eps_tvd, logits, row_thr, row_lse, max_depth, mode, accept_len, path_nodes, emitted, terminal, tvd_used) -> None:
+                eps_tvd, logits, row_thr, row_lse, max_depth, mode, accept_len, path_nodes, emitted, terminal, tvd_used,
+                draft_dist=None) -> None:
     a = select_args()
+    a.draft_dist = _ptr(draft_dist)
     a.n_prompts, a.n_nodes_total, a.vocab, a.max_depth, a.mode = node_off.numel() - 1, token.numel(), logits.shape[1], max_depth, mode
     a.node_off, a.parent, a.token = _ptr(node_off), _ptr(parent), _ptr(token)
     a.q_tok, a.m_int, a.m_conv, a.n_int, a.n_conv = _ptr(q_tok), _ptr(m_int), _ptr(m_conv), _ptr(n_int), _ptr(n_conv)
@@ -332,16 +336,16 @@ class DeviceStep:
                            cfg_scale=self.inp.cfg_scale, temperature=self.inp.temperature, top_k=self.inp.top_k,
                            logits=self.logits, row_max=self.row_max, row_thr=self.row_thr, row_lse=self.row_lse)
 
-    def accept(self, tau_pos=None, tau_seq=None):
-        cascade_accept(self.ctx, node_off=self.node_off, parent=self.parent, token=self.token, h_cond=self.h_cond,
+    def accept(self, tau_pos=None, tau_seq=None, feature_space=FEATURES_HIDDEN):
+        cascade_accept(self.ctx, feature_space=feature_space, node_off=self.node_off, parent=self.parent, token=self.token, h_cond=self.h_cond,
                        logits=self.logits, row_thr=self.row_thr, row_lse=self.row_lse,
                        tau_pos=self.inp.tau_pos if tau_pos is None else tau_pos,
                        tau_seq=self.inp.tau_seq if tau_seq is None else tau_seq,
                        q_tok=self.q_tok, m_int=self.m_int, m_conv=self.m_conv, cos_parent=self.cos_parent,
                        n_int=self.n_int, n_conv=self.n_conv)
 
-    def select(self, mode=WALK_SEQUENTIAL, eps_tvd=None):
-        select_path(self.ctx, node_off=self.node_off, parent=self.parent, token=self.token, q_tok=self.q_tok,
+    def select(self, mode=WALK_SEQUENTIAL, eps_tvd=None, draft_dist=None):
+        select_path(self.ctx, draft_dist=draft_dist, node_off=self.node_off, parent=self.parent, token=self.token, q_tok=self.q_tok,
                     m_int=self.m_int, m_conv=self.m_conv, n_int=self.n_int, n_conv=self.n_conv,
                     draft_prob=self.draft_prob, u=self.u, u_bonus=self.u_bonus,
                     eps_tvd=self.inp.eps_tvd if eps_tvd is None else eps_tvd, logits=self.logits,

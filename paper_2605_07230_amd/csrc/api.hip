@@ -209,8 +209,18 @@ int cascade_pack_lmhead_w(cascade_ctx* ctx, const void* w, int32_t vocab, int32_
   return e == hipSuccess ? CASCADE_OK : hip_fail(e);
 }
 
-int cascade_accept(cascade_ctx* ctx, const accept_args* a) {
-  if (!ctx || !a) return CASCADE_EINVAL;
+int cascade_accept(cascade_ctx* ctx, const accept_args* a_in) {
+  if (!ctx || !a_in) return CASCADE_EINVAL;
+  accept_args local = *a_in;
+  if (local.feature_space == CASCADE_FEATURES_LOGITS) {
+    // similarity measured on the mixed logits: the same kernels with the logits rows as features
+    local.h_cond = local.logits;
+    local.h_dtype = CASCADE_F32;
+    local.hidden = local.vocab;
+  } else if (local.feature_space != CASCADE_FEATURES_HIDDEN) {
+    return CASCADE_EINVAL;
+  }
+  const accept_args* a = &local;
   if (!a->node_off || !a->parent || !a->token || !a->h_cond || !a->logits || !a->row_thr || !a->row_lse || !a->q_tok ||
       !a->m_int || !a->m_conv || !a->cos_parent || !a->n_int || !a->n_conv)
     return CASCADE_EINVAL;
@@ -218,7 +228,8 @@ int cascade_accept(cascade_ctx* ctx, const accept_args* a) {
   if (a->n_prompts < 0 || a->n_nodes_total < 0 || a->hidden <= 0 || a->vocab <= 0) return CASCADE_EINVAL;
   if (bad_float(a->tau_pos) || bad_float(a->tau_seq)) return CASCADE_EINVAL;
   const cascade_limits& L = ctx->lim;
-  if (a->n_nodes_total > L.max_nodes_total || a->hidden > L.hidden || a->vocab > L.vocab) return CASCADE_ESHAPE;
+  const bool on_logits = a->feature_space == CASCADE_FEATURES_LOGITS;
+  if (a->n_nodes_total > L.max_nodes_total || (!on_logits && a->hidden > L.hidden) || a->vocab > L.vocab) return CASCADE_ESHAPE;
   if (a->h_dtype == CASCADE_BF16 && (a->hidden % 8)) return CASCADE_ESHAPE;
   if (a->n_prompts == 0 || a->n_nodes_total == 0) return CASCADE_OK;
   hipError_t e = launch_accept(ctx, a);
@@ -236,8 +247,13 @@ int select_path(cascade_ctx* ctx, const select_args* a) {
   if (bad_float(a->eps_tvd) || a->eps_tvd < 0.f) return CASCADE_EINVAL;
   const cascade_limits& L = ctx->lim;
   if (a->n_nodes_total > L.max_nodes_total || a->vocab > L.vocab || a->max_depth > CASCADE_MAX_DEPTH) return CASCADE_ESHAPE;
+  if (a->draft_dist) {
+    if (a->mode != CASCADE_WALK_SEQUENTIAL) return CASCADE_EINVAL;
+    if (a->vocab % 4) return CASCADE_ESHAPE;
+    if (((uintptr_t)a->draft_dist | (uintptr_t)a->logits) & 15) return CASCADE_EINVAL;
+  }
   if (a->n_prompts == 0) return CASCADE_OK;
-  hipError_t e = launch_select(ctx, a);
+  hipError_t e = a->draft_dist ? launch_select_residual(ctx, a) : launch_select(ctx, a);
   return e == hipSuccess ? CASCADE_OK : hip_fail(e);
 }
 

@@ -62,6 +62,7 @@ hipError_t launch_row_stats(cascade_ctx* ctx, const lmhead_args* a);
 hipError_t launch_pack_w(cascade_ctx* ctx, const void* w, int vocab, int hidden, void* w_packed);
 hipError_t launch_accept(cascade_ctx* ctx, const accept_args* a);
 hipError_t launch_select(cascade_ctx* ctx, const select_args* a);
+hipError_t launch_select_residual(cascade_ctx* ctx, const select_args* a);
 hipError_t launch_kv_commit(cascade_ctx* ctx, const kv_commit_args* a);
 
 // ----------------------------------------------------------------------------------------------

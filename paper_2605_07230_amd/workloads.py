@@ -444,3 +444,37 @@ def make_commit_inputs(inp: VerifyInputs, n_layers: int, seed: int = 0, slack: i
     accept_len, path_nodes = random_paths(inp, seed)
     return CommitInputs(n_layers=n_layers, k_tree=k_tree, v_tree=v_tree, k_cache=k_cache, v_cache=v_cache, prefix_cap=cap,
                         row_prompt=row_prompt, accept_len=accept_len, path_nodes=path_nodes)
+
+
+# ------------------------------------------------------------------------------------------------
+# full drafter distributions for the residual walk
+
+def make_draft_dist(inp: VerifyInputs, seed: int = 0, zipf_s: float = 1.1) -> np.ndarray:
+    """[N_c, V] float32: the children of one parent share a row, a Zipf(zipf_s) law over a vocabulary
+    permutation drawn per parent, with each child's own token moved to a seeded rank among the
+    first 32 (so drafted tokens carry visible drafter mass).  Root rows are uniform (never read)."""
+    rng = np.random.default_rng(seed + 31337)
+    V, N = inp.vocab, inp.n_nodes
+    ranks = np.arange(1, V + 1, dtype=np.float64)
+    pmf = ranks ** (-zipf_s)
+    pmf = (pmf / pmf.sum()).astype(np.float32)
+    out = np.empty((N, V), dtype=np.float32)
+    for b in range(inp.n_prompts):
+        lo, hi = int(inp.node_off[b]), int(inp.node_off[b + 1])
+        par = inp.parent[lo:hi]
+        out[lo] = np.float32(1.0 / V)
+        for p in range(hi - lo):
+            kids = np.nonzero(par == p)[0]
+            if len(kids) == 0:
+                continue
+            perm = rng.permutation(V)
+            # move the children's tokens to distinct early ranks
+            slots = rng.choice(min(32, V), size=min(len(kids), min(32, V)), replace=False)
+            for kid, slot in zip(kids, slots):
+                t = int(inp.token[lo + kid])
+                j = int(np.nonzero(perm == t)[0][0])
+                perm[j], perm[slot] = perm[slot], perm[j]
+            row = np.empty(V, dtype=np.float32)
+            row[perm] = pmf
+            out[lo + kids] = row
+    return out
