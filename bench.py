@@ -85,6 +85,7 @@ def main() -> int:
     ap.add_argument("--row-major-w", action="store_true", help="keep the LM-head matrix row-major (default: packed once, as at model load)")
     ap.add_argument("--cache-warm", action="store_true", help="also time the steps on one copy of the inputs (served from the last-level cache)")
     ap.add_argument("--commit-layers", type=int, default=30, help="decoder layers in the separately timed KV commit (0: skip)")
+    ap.add_argument("--weights-seqs", type=int, default=8, help="sequences in the separately timed Eq. 4 weight mask (0: skip)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -184,6 +185,26 @@ def main() -> int:
         commit = {"layers": Lc, "us": ms * 1e3 / n, "bytes": moved, "GBs": moved / (ms * 1e-3 / n) / 1e9}
         del kt, vt, kc, vc
 
+    # the Eq. 4 weight mask (drafter-training side, not part of the step metric): Lumina-shaped
+    # sequences, one pass over [8, 2356, hidden] features; HBM-bound, rotated over 4 copies
+    weights = None
+    if args.weights_seqs > 0:
+        Bw, Kw = args.weights_seqs, 2356
+        feats = [torch.randn((Bw, Kw, inp.hidden), device="cuda").to(torch.bfloat16) for _ in range(4)]
+        wout = torch.empty((Bw, Kw), dtype=torch.float32, device="cuda")
+        ds.ctx.set_kernel_timing(True)
+        for i in range(44):
+            binding.convergence_weights(ds.ctx, features=feats[i % 4], tau_seq=0.9, c=2.0, weights=wout)
+            if i == 3:
+                ds.ctx.read_kernel_timing(7)
+        ms, n = ds.ctx.read_kernel_timing(7)
+        ds.ctx.set_kernel_timing(False)
+        nbytes_w = Bw * Kw * inp.hidden * 2 + Bw * Kw * 4
+        gbs = nbytes_w / (ms * 1e-3 / n) / 1e9
+        weights = {"seqs": Bw, "seq_len": Kw, "hidden": inp.hidden, "us": ms * 1e3 / n, "bytes": nbytes_w, "GBs": gbs,
+                   "hbm_frac": gbs / HBM_PEAK_GBS}
+        del feats
+
     # what this device sustains: a plain streaming read of 1 GiB and a register-only MFMA loop
     big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     big.zero_()
@@ -235,6 +256,7 @@ def main() -> int:
                           / HBM_PEAK_GBS) if kernel_us.get("attn") else None,
         "accept_len": ds.accept_len.cpu().tolist(),
         "kv_commit": commit,
+        "convergence_weights": weights,
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -106,7 +106,8 @@ typedef enum {
   CASCADE_K_ACCEPT = 4,
   CASCADE_K_SELECT = 5,
   CASCADE_K_COMMIT = 6,      /* kv_commit */
-  CASCADE_K_COUNT = 7
+  CASCADE_K_WEIGHTS = 7,     /* convergence_weights */
+  CASCADE_K_COUNT = 8
 } cascade_kernel_id;
 int cascade_set_kernel_timing(cascade_ctx* ctx, int enable);
 int cascade_read_kernel_timing(cascade_ctx* ctx, int kernel_id, double* total_ms, int32_t* launches);
@@ -321,6 +322,29 @@ typedef struct {
   int32_t* prefix_len_out;      /* [n_rows] DEVICE */
 } kv_commit_args;
 int kv_commit(cascade_ctx* ctx, const kv_commit_args* args);
+
+/* ---------------------------------------------------------------------------------------------
+ * convergence_weights — the weight mask of the drafter-training loss (Sec. "Enhancing Drafter
+ * Performance", Eq. 4): over a full target-generated sequence, position k's soft cross-entropy
+ * term is weighted by c when the consecutive target predictions (k, k+1) are in the convergence
+ * set, i.e. cos(F_k, F_{k+1}) >= tau_seq (Eq. 2 between neighbours), and by 1 otherwise (c = 2 in
+ * App. "Configuration Details").  The last position has no successor: weight 1.
+ *
+ *     features [n_seqs, seq_len, hidden] dtype, contiguous; hidden * sizeof(dtype) a multiple of 16
+ *              and at most 16384 bytes
+ *     weights  [n_seqs, seq_len] float32
+ *     cos_next [n_seqs, seq_len] float32, cos(F_k, F_{k+1}); 0 at the last position; may be NULL
+ * Dot products and norms accumulate in float32; cos is 0 when a norm is 0.
+ */
+typedef struct {
+  cascade_dtype dtype;
+  int32_t n_seqs, seq_len, hidden;
+  const void* features;
+  float tau_seq, c;
+  float* weights;
+  float* cos_next;            /* nullable */
+} conv_weight_args;
+int convergence_weights(cascade_ctx* ctx, const conv_weight_args* args);
 
 #ifdef __cplusplus
 }

@@ -25,7 +25,7 @@ OK, EINVAL, ESHAPE, EDTYPE, ENOMEM, EHIP, ETREE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["cascade_create", "cascade_destroy", "cascade_strerror", "cascade_device_status", "cascade_workspace_bytes",
            "cascade_set_kernel_timing", "cascade_read_kernel_timing", "cascade_measure_hbm_read",
-           "cascade_measure_mfma_bf16", "cascade_pack_lmhead_w", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path", "kv_commit"]
+           "cascade_measure_mfma_bf16", "cascade_pack_lmhead_w", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path", "kv_commit", "convergence_weights"]
 
 _vp, _i32, _i64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
 
@@ -72,6 +72,11 @@ class kv_commit_args(C.Structure):
                 ("cache_stride_pos", _i64), ("prefix_cap", _i32), ("prefix_len", _vp), ("prefix_len_out", _vp)]
 
 
+class conv_weight_args(C.Structure):
+    _fields_ = [("dtype", C.c_int), ("n_seqs", _i32), ("seq_len", _i32), ("hidden", _i32), ("features", _vp),
+                ("tau_seq", _f32), ("c", _f32), ("weights", _vp), ("cos_next", _vp)]
+
+
 _lib = None
 
 
@@ -105,7 +110,8 @@ def load_library() -> C.CDLL:
     lib.cascade_pack_lmhead_w.argtypes = [_vp, _vp, _i32, _i32, _vp]
     lib.cascade_pack_lmhead_w.restype = C.c_int
     for name, st in (("tree_verify_attn", tree_attn_args), ("lmhead_softmax_cfg", lmhead_args),
-                     ("cascade_accept", accept_args), ("select_path", select_args), ("kv_commit", kv_commit_args)):
+                     ("cascade_accept", accept_args), ("select_path", select_args), ("kv_commit", kv_commit_args),
+                     ("convergence_weights", conv_weight_args)):
         fn = getattr(lib, name)
         fn.argtypes = [_vp, C.POINTER(st)]
         fn.restype = C.c_int
@@ -272,6 +278,17 @@ def kv_commit(ctx: Context, *, node_off, row_prompt, accept_len, path_nodes, k_t
     a.prefix_cap = k_cache.shape[3]
     a.prefix_len, a.prefix_len_out = _ptr(prefix_len), _ptr(prefix_len_out)
     _check(ctx.lib.kv_commit(ctx.handle, C.byref(a)))
+
+
+def convergence_weights(ctx: Context, *, features, tau_seq: float, c: float, weights, cos_next=None) -> None:
+    """features [B, K, h] contiguous; weights / cos_next [B, K] float32."""
+    a = conv_weight_args()
+    assert features.is_contiguous()
+    a.dtype = _dtype_code(features)
+    a.n_seqs, a.seq_len, a.hidden = features.shape
+    a.features, a.tau_seq, a.c = _ptr(features), tau_seq, c
+    a.weights, a.cos_next = _ptr(weights), _ptr(cos_next)
+    _check(ctx.lib.convergence_weights(ctx.handle, C.byref(a)))
 
 
 # ------------------------------------------------------------------------------------------------

@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcascade_verify.so")
-SOURCES = ["api.hip", "attn.hip", "lmhead.hip", "accept.hip", "select.hip", "select_residual.hip", "commit.hip", "calib.hip"]
+SOURCES = ["api.hip", "attn.hip", "lmhead.hip", "accept.hip", "select.hip", "select_residual.hip", "commit.hip", "weights.hip", "calib.hip"]
 # packed fp32 VALU forms are switched off for all device code
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
                 "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

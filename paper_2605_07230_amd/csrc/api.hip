@@ -282,4 +282,19 @@ int kv_commit(cascade_ctx* ctx, const kv_commit_args* a) {
   return err == hipSuccess ? CASCADE_OK : hip_fail(err);
 }
 
+int convergence_weights(cascade_ctx* ctx, const conv_weight_args* a) {
+  if (!ctx || !a) return CASCADE_EINVAL;
+  if (!a->features || !a->weights) return CASCADE_EINVAL;
+  if (a->dtype != CASCADE_F32 && a->dtype != CASCADE_BF16) return CASCADE_EDTYPE;
+  if (a->n_seqs < 0 || a->seq_len < 0 || a->hidden <= 0) return CASCADE_EINVAL;
+  if (bad_float(a->tau_seq) || bad_float(a->c)) return CASCADE_EINVAL;
+  const int64_t row_bytes = (int64_t)a->hidden * (a->dtype == CASCADE_BF16 ? 2 : 4);
+  if ((row_bytes % 16) || row_bytes > 16384) return CASCADE_ESHAPE;
+  if ((uintptr_t)a->features & 15) return CASCADE_EINVAL;
+  if ((int64_t)a->n_seqs * ((a->seq_len + 7) / 8 + 1) > 0x3fffffff) return CASCADE_ESHAPE;
+  if (a->n_seqs == 0 || a->seq_len == 0) return CASCADE_OK;
+  hipError_t err = launch_conv_weights(ctx, a);
+  return err == hipSuccess ? CASCADE_OK : hip_fail(err);
+}
+
 }  // extern "C"

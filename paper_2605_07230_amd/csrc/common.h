@@ -23,7 +23,7 @@ struct cascade_ctx {
   // optional per-kernel timing with HIP events on the ctx stream (cascade_set_kernel_timing)
   bool timing;
   hipEvent_t* ev;         // [CASCADE_K_COUNT][TIMING_RING][2], created on first enable
-  int ev_used[8];
+  int ev_used[CASCADE_K_COUNT];
 };
 
 enum { TIMING_RING = 2048 };
@@ -64,6 +64,7 @@ hipError_t launch_accept(cascade_ctx* ctx, const accept_args* a);
 hipError_t launch_select(cascade_ctx* ctx, const select_args* a);
 hipError_t launch_select_residual(cascade_ctx* ctx, const select_args* a);
 hipError_t launch_kv_commit(cascade_ctx* ctx, const kv_commit_args* a);
+hipError_t launch_conv_weights(cascade_ctx* ctx, const conv_weight_args* a);
 
 // ----------------------------------------------------------------------------------------------
 // device helpers

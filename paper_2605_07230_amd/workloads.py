@@ -478,3 +478,24 @@ def make_draft_dist(inp: VerifyInputs, seed: int = 0, zipf_s: float = 1.1) -> np
             row[perm] = pmf
             out[lo + kids] = row
     return out
+
+
+# ------------------------------------------------------------------------------------------------
+# target feature sequences for the Eq. 4 weight mask
+
+def make_feature_sequence(n_seqs: int, seq_len: int, hidden: int, dtype: str = "bf16", seed: int = 0,
+                          p_stay: float = 0.6, sigmas=(0.1, 0.2, 0.3, 0.6)) -> np.ndarray:
+    """[n_seqs, seq_len, hidden] float32 (bf16-rounded for dtype "bf16"): a sequence of image
+    positions in which, with probability p_stay, a position's feature is its predecessor's plus
+    sigma * N(0,1) (a semantically uniform region; cos about 0.995 / 0.98 / 0.96 / 0.86) and
+    otherwise a fresh N(0,1) draw (a region boundary)."""
+    rng = np.random.default_rng(seed + 555)
+    out = np.empty((n_seqs, seq_len, hidden), dtype=np.float32)
+    for b in range(n_seqs):
+        for k in range(seq_len):
+            if k > 0 and rng.random() < p_stay:
+                sigma = np.float32(sigmas[int(rng.integers(0, len(sigmas)))])
+                out[b, k] = out[b, k - 1] + sigma * _randn(rng, hidden)
+            else:
+                out[b, k] = _randn(rng, hidden)
+    return round_bf16(out) if dtype == "bf16" else out

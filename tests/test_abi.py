@@ -38,11 +38,12 @@ def test_every_declared_symbol_is_exported(lib):
 def test_struct_layout_matches_the_header(tmp_path):
     from paper_2605_07230_amd import binding
     src = tmp_path / "sizes.c"
-    structs = ["cascade_limits", "tree_attn_args", "lmhead_args", "accept_args", "select_args", "kv_commit_args"]
+    structs = ["cascade_limits", "tree_attn_args", "lmhead_args", "accept_args", "select_args", "kv_commit_args", "conv_weight_args"]
     body = "\n".join(f'  printf("{s} %zu\\n", sizeof({s}));' for s in structs)
     probes = [("tree_attn_args", "lse"), ("tree_attn_args", "cache_stride_row"), ("lmhead_args", "row_lse"),
               ("accept_args", "n_conv"), ("select_args", "tvd_used"), ("select_args", "eps_tvd"),
-              ("kv_commit_args", "cache_stride_layer"), ("kv_commit_args", "prefix_len_out")]
+              ("kv_commit_args", "cache_stride_layer"), ("kv_commit_args", "prefix_len_out"),
+              ("conv_weight_args", "cos_next"), ("accept_args", "feature_space"), ("select_args", "draft_dist")]
     body += "\n" + "\n".join(f'  printf("{s}.{f} %zu\\n", offsetof({s}, {f}));' for s, f in probes)
     src.write_text(f'#include <stdio.h>\n#include <stddef.h>\n#include "{HEADER}"\nint main(void) {{\n{body}\n  return 0;\n}}\n')
     exe = tmp_path / "sizes"
@@ -64,6 +65,7 @@ def test_host_side_errors_without_a_gpu(lib):
     assert lib.cascade_accept(None, None) == binding.EINVAL
     assert lib.select_path(None, None) == binding.EINVAL
     assert lib.kv_commit(None, None) == binding.EINVAL
+    assert lib.convergence_weights(None, None) == binding.EINVAL
     assert lib.cascade_measure_mfma_bf16(None, 1, None) == binding.EINVAL
     assert lib.cascade_measure_hbm_read(None, None, 0, 1, None) == binding.EINVAL
     assert lib.cascade_destroy(None) == binding.EINVAL
