@@ -86,6 +86,7 @@ def main() -> int:
     ap.add_argument("--cache-warm", action="store_true", help="also time the steps on one copy of the inputs (served from the last-level cache)")
     ap.add_argument("--commit-layers", type=int, default=30, help="decoder layers in the separately timed KV commit (0: skip)")
     ap.add_argument("--weights-seqs", type=int, default=8, help="sequences in the separately timed Eq. 4 weight mask (0: skip)")
+    ap.add_argument("--decode-image", type=int, default=576, help="tokens of the separately timed multi-step decode loop (0: skip)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -205,6 +206,23 @@ def main() -> int:
                    "hbm_frac": gbs / HBM_PEAK_GBS}
         del feats
 
+    # chained steps through the KV commit until a whole image is formed (context only: synthetic
+    # step inputs cycled from a pool; the host reads the accepted length back after every step)
+    loop_out = None
+    if args.decode_image > 0 and inp.n_prompts == 1:
+        from paper_2605_07230_amd import decode
+        pool = [inp] + [wl.make_config(args.workload, args.seed + 1 + i) for i in range(3)]
+        for p_ in pool[1:]:
+            p_.w = inp.w
+        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed)
+        loop.run(max_steps=5)                           # warm-up
+        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed)
+        lr = loop.run()
+        loop_out = {"image_tokens": args.decode_image, "steps": lr.steps, "tokens": lr.tokens,
+                    "mean_accept_len": lr.mean_accept_len, "tvd_per_image": lr.tvd_per_image,
+                    "ms_per_image": lr.seconds * 1e3, "ms_per_step": lr.seconds * 1e3 / max(lr.steps, 1)}
+        del loop
+
     # what this device sustains: a plain streaming read of 1 GiB and a register-only MFMA loop
     big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     big.zero_()
@@ -257,6 +275,7 @@ def main() -> int:
         "accept_len": ds.accept_len.cpu().tolist(),
         "kv_commit": commit,
         "convergence_weights": weights,
+        "decode_loop": loop_out,
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
