@@ -86,7 +86,7 @@ def main() -> int:
     ap.add_argument("--cache-warm", action="store_true", help="also time the steps on one copy of the inputs (served from the last-level cache)")
     ap.add_argument("--commit-layers", type=int, default=30, help="decoder layers in the separately timed KV commit (0: skip)")
     ap.add_argument("--weights-seqs", type=int, default=8, help="sequences in the separately timed Eq. 4 weight mask (0: skip)")
-    ap.add_argument("--decode-image", type=int, default=576, help="tokens of the separately timed multi-step decode loop (0: skip)")
+    ap.add_argument("--decode-image", type=int, default=0, help="tokens of the separately timed multi-step decode loop (0: skip)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:

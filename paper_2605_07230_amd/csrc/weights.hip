@@ -2,7 +2,7 @@
 // consecutive positions (k, k+1) of a target-generated sequence: cos(F_k, F_{k+1}) >= tau_seq (the
 // convergence set of Eq. 2 between neighbours) gives weight c, otherwise 1.
 //
-// Bandwidth-bound: every feature row should cross HBM once.  One wavefront walks a run of RUN
+// Bandwidth-bound: every feature row should cross HBM once.  One wavefront walks a run of
 // consecutive pairs with the previous row held in registers (16-byte vectors, lane-interleaved so
 // that every load instruction covers 1 KiB of contiguous memory), the next row already requested
 // while the current one is reduced; only the first row of a run is read by two wavefronts.
@@ -11,7 +11,6 @@
 namespace {
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-constexpr int RUN = 8;   // pairs per wavefront
 
 template <typename T> struct Acc;
 template <> struct Acc<float> {
@@ -40,7 +39,7 @@ template <> struct Acc<uint16_t> {   // bf16 pairs packed in 32-bit words
 
 // NV = 16-byte vectors per lane (row bytes <= NV * 1024)
 template <typename T, int NV>
-__global__ __launch_bounds__(256) void conv_weight_kernel(conv_weight_args a, int runs_per_seq) {
+__global__ __launch_bounds__(256) void conv_weight_kernel(conv_weight_args a, int runs_per_seq, int RUN) {
   const int lane = threadIdx.x & 63;
   const long long wave_id = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int seq = (int)(wave_id / runs_per_seq), run = (int)(wave_id % runs_per_seq);
@@ -71,7 +70,7 @@ __global__ __launch_bounds__(256) void conv_weight_kernel(conv_weight_args a, in
     for (int v = 0; v < NV; ++v) Acc<T>::dot(prev[v], prev[v], dummy, pp);
     pp = wave_sum(pp);
     for (int k = k0; k < k1; ++k) {
-      const int kn = min(k + 2, K - 1);   // next row to fetch (a valid row even past the run)
+      const int kn = min(k + 2, k1);   // next row to fetch; at the end of the run the last row again (a cache hit)
       load_row(kn, nxt);
       float ab = 0.f, bb = 0.f;
 #pragma unroll
@@ -98,10 +97,15 @@ template <typename T>
 hipError_t launch_t(cascade_ctx* ctx, const conv_weight_args* a) {
   const int row_bytes = a->hidden * (int)sizeof(T);
   const int nv = (row_bytes + 1023) / 1024;
+  // pairs per wavefront: long runs re-read fewer boundary rows, short runs give more wavefronts in
+  // flight; aim at eight wavefronts per compute unit, between 8 and 32 pairs each
+  const long long pairs = (long long)a->n_seqs * (a->seq_len > 1 ? a->seq_len - 1 : 0);
+  int RUN = (int)(pairs / (256 * 8));
+  RUN = RUN < 8 ? 8 : (RUN > 32 ? 32 : RUN);
   const int runs_per_seq = a->seq_len > 1 ? (a->seq_len - 1 + RUN - 1) / RUN : 1;
   const long long waves = (long long)a->n_seqs * runs_per_seq;
   dim3 grid((unsigned)((waves + 3) / 4));
-#define CASCADE_LAUNCH_CW(NV) hipLaunchKernelGGL((conv_weight_kernel<T, NV>), grid, dim3(256), 0, ctx->stream, *a, runs_per_seq)
+#define CASCADE_LAUNCH_CW(NV) hipLaunchKernelGGL((conv_weight_kernel<T, NV>), grid, dim3(256), 0, ctx->stream, *a, runs_per_seq, RUN)
   if (nv <= 1) CASCADE_LAUNCH_CW(1);
   else if (nv <= 2) CASCADE_LAUNCH_CW(2);
   else if (nv <= 4) CASCADE_LAUNCH_CW(4);
