@@ -1,15 +1,15 @@
-// cascade_accept kernels for gfx950 (Sec. 4.1 cosine similarity of target hidden states; Eq. 1
+// cascade_accept kernel for gfx950 (Sec. 4.1 cosine similarity of target hidden states; Eq. 1
 // interchangeable set; Eq. 2 convergence set; Eq. 3 aggregated mass).
 //
-// Kernel 1, one workgroup per parent node p: the Gram matrix of the rows [F_p, F_child_1 ..
-// F_child_k] gives every cosine the children of p need at once — sibling/sibling (Eq. 1) and
-// parent/child (Eq. 2).  For bf16 hidden states it is a dense contraction and runs on
-// v_mfma_f32_16x16x32_bf16 (16 x 16 row blocks, operands loaded straight from global memory as
-// 16-byte k-contiguous pieces); for f32 it is plain wave-wide dot products.  The workgroup then
-// forms I_a for each child a, sums the mass of its distinct tokens under p's distribution, and
-// writes q_tok, m_int, n_int, cos_parent and a 64-bit membership mask of I_a (by sibling rank).
-// Kernel 2, one wavefront per node a: C_a from cos_parent of a's children, then m_conv over the
-// distinct tokens not already counted (a's own token, tokens of I_a), and n_conv.
+// One workgroup per node a.  Everything a needs is the cosine of its own feature row against its
+// parent, its siblings and its children: one row against at most 1 + 63 + 64 others.  The others
+// are taken in blocks of 15; with a as the 16th row, one 16 x 16 Gram tile per block gives every
+// a . x (row of a) and every |x|^2 (diagonal) at once.  For bf16 hidden states the tile runs on
+// v_mfma_f32_16x16x32_bf16 with the four waves splitting the hidden dimension (operands loaded
+// straight from global memory as 16-byte k-contiguous pieces); f32 rows (and logit-space
+// similarity) use wave-wide dot products.  The probabilities of the siblings' and children's
+// tokens under the parent's distribution are gathered while the rows are still in flight; the sets
+// I_a and C_a, the distinct-token masses and all outputs then need only ballots and LDS.
 #include "common.h"
 
 namespace {
@@ -75,213 +75,215 @@ __device__ __forceinline__ f32x4 gram_tile(const uint16_t* rowa, const uint16_t*
   return acc;
 }
 
+// a . x and x . x in one pass (generic rows)
+__device__ __forceinline__ void dot2_rows(const float* a, const float* x, int h, int lane, float& ax, float& xx) {
+  float s = 0.f, t = 0.f;
+  for (int k = lane; k < h; k += 64) {
+    const float xv = x[k];
+    s = fmaf(a[k], xv, s);
+    t = fmaf(xv, xv, t);
+  }
+  ax = wave_sum(s);
+  xx = wave_sum(t);
+}
+__device__ __forceinline__ void dot2_rows(const uint16_t* a, const uint16_t* x, int h, int lane, float& ax, float& xx) {
+  float s = 0.f, t = 0.f;
+  for (int k = lane * 8; k < h; k += 64 * 8) {   // h is a multiple of 8
+    const uint4 ua = *(const uint4*)(a + k), ux = *(const uint4*)(x + k);
+    const uint32_t wa[4] = {ua.x, ua.y, ua.z, ua.w}, wx[4] = {ux.x, ux.y, ux.z, ux.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float x0 = __uint_as_float(wx[i] << 16), x1 = __uint_as_float(wx[i] & 0xffff0000u);
+      s = fmaf(__uint_as_float(wa[i] << 16), x0, s);
+      s = fmaf(__uint_as_float(wa[i] & 0xffff0000u), x1, s);
+      t = fmaf(x0, x0, t);
+      t = fmaf(x1, x1, t);
+    }
+  }
+  ax = wave_sum(s);
+  xx = wave_sum(t);
+}
+
+constexpr int MAXO = 2 * MAXW;   // others of a node: parent + (siblings - 1) + children <= 1 + 63 + 64
+
 template <typename T>
-__global__ __launch_bounds__(256) void accept_gram_kernel(accept_args a, unsigned long long* imask, int* dev_status) {
-  __shared__ float gfull[GN * GP];        // Gram matrix; for MFMA tiles only blocks (bi <= bj) are filled
-  __shared__ float gq[4][256];            // K-quarter partial tiles when there is a single 16 x 16 block
-  __shared__ int s_child[MAXW];
-  __shared__ int s_tok[MAXW];
-  __shared__ int s_k;
+__global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* dev_status) {
+  __shared__ float gq[4][256];          // K-quarter partial Gram tiles
+  __shared__ float s_cos[MAXO];         // cos(a, other)
+  __shared__ int s_other[MAXO];         // node index of every other row: parent, siblings (without a), children
+  __shared__ int s_stok[MAXW], s_ctok[MAXW];   // tokens of the siblings (by rank, a included) and of the children
+  __shared__ int s_chl[MAXW];                  // the children's node indices
+  __shared__ float s_sq[MAXW], s_cq[MAXW];     // their probabilities under the parent's distribution
+  __shared__ int s_ks, s_kc, s_rank;
+  __shared__ float s_aa;                       // |a|^2 (generic path)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int b = blockIdx.y, p = blockIdx.x;
+  const int b = blockIdx.y, node = blockIdx.x;
   const int lo = a.node_off[b], Tn = a.node_off[b + 1] - lo;
-  if (p >= Tn) return;
+  if (node >= Tn) return;
+  const int64_t gi = lo + node;
+  const int par = a.parent[gi];
+  auto write_zero = [&]() {
+    if (tid == 0) {
+      a.q_tok[gi] = 0.f; a.m_int[gi] = 0.f; a.cos_parent[gi] = 0.f; a.n_int[gi] = 0;
+      a.m_conv[gi] = 0.f; a.n_conv[gi] = 0;
+    }
+  };
+  if (node == 0 || par < 0 || par >= node) {   // roots, and nodes whose parent pointer is unusable
+    if (tid == 0 && (node > 0 || par != -1)) atomicOr(dev_status, CASCADE_FLAG_PARENT);
+    write_zero();
+    return;
+  }
   const int h = a.hidden;
   const T* H = (const T*)a.h_cond;
+  const float* Lp = a.logits + (int64_t)(lo + par) * a.vocab;
+  const float thr = a.row_thr[lo + par], lse = a.row_lse[lo + par];
 
-  if (wave == 0) {   // ordered list of p's children
-    int k = 0;
-    for (int base = (p + 1) & ~63; base < Tn; base += 64) {
+  if (wave == 0) {   // siblings (children of par, in index order, a included) and children of a
+    int ks = 0, kc = 0, rank = -1;
+    for (int base = 0; base < Tn; base += 64) {   // from chunk 0: these loads do not wait for par
       const int j = base + lane;
-      const bool is = j < Tn && j > p && a.parent[lo + j] == p;
-      const unsigned long long m = __ballot(is);
-      if (is) {
-        const int idx = k + __popcll(m & ((1ull << lane) - 1ull));
-        if (idx < MAXW) { s_child[idx] = j; s_tok[idx] = a.token[lo + j]; }
+      const int pj = j < Tn ? a.parent[lo + j] : -2;
+      const bool sib = pj == par && j > par;
+      const unsigned long long sm = __ballot(sib);
+      if (sib) {
+        const int r = ks + __popcll(sm & ((1ull << lane) - 1ull));
+        if (r < MAXW) {
+          const int t = a.token[lo + j];
+          s_stok[r] = t;
+          s_sq[r] = (t >= 0 && t < a.vocab) ? prob_of(Lp, thr, lse, t) : 0.f;
+          // other index: parent is 0; siblings keep their rank order with a left out
+          if (j != node) s_other[1 + r - (j > node ? 1 : 0)] = j;
+        }
+        if (j == node) rank = r;
       }
-      k += __popcll(m);
+      ks += __popcll(sm);
+      const bool ch = pj == node && j > node;
+      const unsigned long long cm = __ballot(ch);
+      if (ch) {
+        const int r = kc + __popcll(cm & ((1ull << lane) - 1ull));
+        if (r < MAXW) {
+          const int t = a.token[lo + j];
+          s_ctok[r] = t;
+          s_cq[r] = (t >= 0 && t < a.vocab) ? prob_of(Lp, thr, lse, t) : 0.f;
+          s_chl[r] = j;
+        }
+      }
+      kc += __popcll(cm);
     }
-    if (k > MAXW) {
+    rank = wave_max_i(rank);
+    if (ks > MAXW || kc > MAXW) {
       if (lane == 0) atomicOr(dev_status, CASCADE_FLAG_WIDTH);
-      k = MAXW;
+      ks = min(ks, MAXW);
+      kc = min(kc, MAXW);
     }
-    if (lane == 0) s_k = k;
+    if (lane == 0) { s_ks = ks; s_kc = kc; s_rank = rank; s_other[0] = par; }
   }
   __syncthreads();
-  const int k = s_k;
-  if (k == 0) return;
-  const int n = k + 1, nb = (n + 15) >> 4;
-  auto row_of = [&](int r) -> const T* { return H + (int64_t)(lo + (r == 0 ? p : s_child[r - 1])) * h; };
+  const int ks = s_ks, kc = s_kc, rank = s_rank;
+  if (rank < 0 || rank >= MAXW) {   // beyond the width limit (flagged above): not verified
+    write_zero();
+    return;
+  }
+  const int n_sib = ks - 1;              // siblings without a
+  const int n_other = 1 + n_sib + kc;
+  if (tid < kc) s_other[1 + n_sib + tid] = s_chl[tid];   // the children come after the siblings
+  __syncthreads();
 
+  const T* row_a = H + (int64_t)gi * h;
   bool mfma_done = false;
   if constexpr (sizeof(T) == 2) {
     if ((h & 127) == 0) {
       mfma_done = true;
       const int l16 = lane & 15, g = lane >> 4;
-      if (nb == 1) {
-        // one block: the four waves split the hidden dimension, partial tiles summed in a fixed order
-        const uint16_t* ra = (const uint16_t*)row_of(min(l16, n - 1));
-        const int kq = h / 4;   // a multiple of 32
+      const int kq = h / 4;   // a multiple of 32
+      for (int blk = 0; blk * 15 < n_other; ++blk) {
+        // tile rows: 0 = a, 1..15 = others 15 blk .. 15 blk + 14 (clamped: extra rows repeat the last one)
+        const int o = 15 * blk + l16 - 1;
+        const uint16_t* ra = l16 == 0 ? (const uint16_t*)row_a
+                                      : (const uint16_t*)(H + (int64_t)(lo + s_other[min(o, n_other - 1)]) * h);
         const f32x4 acc = gram_tile(ra, ra, true, wave * kq, (wave + 1) * kq, g);
+        if (blk > 0) __syncthreads();   // the previous block's partial tiles have been consumed
 #pragma unroll
         for (int r = 0; r < 4; ++r) gq[wave][(4 * g + r) * 16 + l16] = acc[r];
         __syncthreads();
-        const int i = tid >> 4, j = tid & 15;
-        if (i < n && j < n) gfull[i * GP + j] = ((gq[0][tid] + gq[1][tid]) + gq[2][tid]) + gq[3][tid];
-      } else {
-        // several blocks: block pairs (bi <= bj) are shared out over the waves, full hidden dimension each
-        const int npairs = nb * (nb + 1) / 2;
-        for (int pi = wave; pi < npairs; pi += 4) {
-          int bi = 0, rem = pi;
-          while (rem >= nb - bi) { rem -= nb - bi; ++bi; }
-          const int bj = bi + rem;
-          const uint16_t* ra = (const uint16_t*)row_of(min(16 * bi + l16, n - 1));
-          const uint16_t* rb = (const uint16_t*)row_of(min(16 * bj + l16, n - 1));
-          const f32x4 acc = gram_tile(ra, rb, bi == bj, 0, h, g);
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int i = 16 * bi + 4 * g + r, j = 16 * bj + l16;
-            if (i < n && j < n) gfull[i * GP + j] = acc[r];
-          }
+        if (tid >= 1 && tid < 16 && 15 * blk + tid - 1 < n_other) {
+          // row 0 of the tile: a . x_j ; diagonal: |x_j|^2 ; entry (0, 0): |a|^2
+          const int j = tid;
+          const float ax = ((gq[0][j] + gq[1][j]) + gq[2][j]) + gq[3][j];
+          const float xx = ((gq[0][17 * j] + gq[1][17 * j]) + gq[2][17 * j]) + gq[3][17 * j];
+          const float aa = ((gq[0][0] + gq[1][0]) + gq[2][0]) + gq[3][0];
+          s_cos[15 * blk + j - 1] = cos_from(ax, aa, xx);
         }
       }
     }
   }
   if (!mfma_done) {
-    const int npairs = n * (n + 1) / 2;
-    for (int pi = wave; pi < npairs; pi += 4) {
-      int i = 0, rem = pi;
-      while (rem >= n - i) { rem -= n - i; ++i; }
-      const int j = i + rem;
-      const float d = dot_rows(row_of(i), row_of(j), h, lane);
-      if (lane == 0) { gfull[i * GP + j] = d; gfull[j * GP + i] = d; }
+    if (wave == 0) {
+      float aa, dummy;
+      dot2_rows(row_a, row_a, h, lane, dummy, aa);
+      if (lane == 0) s_aa = aa;
+    }
+    __syncthreads();
+    for (int oi = wave; oi < n_other; oi += 4) {
+      float ax, xx;
+      dot2_rows(row_a, H + (int64_t)(lo + s_other[oi]) * h, h, lane, ax, xx);
+      if (lane == 0) s_cos[oi] = cos_from(ax, s_aa, xx);
     }
   }
   __syncthreads();
-  // entries (i, j) with i in a later 16-row block than j were produced as (j, i)
-  auto G = [&](int i, int j) -> float { return ((i >> 4) > (j >> 4)) ? gfull[j * GP + i] : gfull[i * GP + j]; };
 
-  const float* Lp = a.logits + (int64_t)(lo + p) * a.vocab;
-  const float thr = a.row_thr[lo + p], lse = a.row_lse[lo + p];
-  const float g00 = G(0, 0);
-  for (int i = wave; i < k; i += 4) {   // child i is row i + 1
-    const int node = s_child[i];
-    const int ta = s_tok[i];
+  if (wave == 0) {
+    const int ta = s_stok[rank];
     const bool tok_ok = ta >= 0 && ta < a.vocab;
-    const float gii = G(i + 1, i + 1);
+    // I_a among the siblings, by rank (lane = rank)
     bool member = false;
     int tj = -1;
-    if (lane < k && lane != i) {
-      tj = s_tok[lane];
-      member = cos_from(G(i + 1, lane + 1), gii, G(lane + 1, lane + 1)) >= a.tau_pos;
+    if (lane < ks && lane != rank) {
+      tj = s_stok[lane];
+      member = s_cos[1 + lane - (lane > rank ? 1 : 0)] >= a.tau_pos;
     }
-    const unsigned long long mask = __ballot(member);
-    float mass = 0.f;
+    const unsigned long long imask = __ballot(member);
+    float mi = 0.f;
     if (member && tj != ta && tj >= 0 && tj < a.vocab) {
       bool dup = false;
-      for (unsigned long long m = mask & ((1ull << lane) - 1ull); m; m &= m - 1) dup |= (s_tok[__ffsll((long long)m) - 1] == tj);
-      if (!dup) mass = prob_of(Lp, thr, lse, tj);
+      for (unsigned long long m = imask & ((1ull << lane) - 1ull); m; m &= m - 1) dup |= (s_stok[__ffsll((long long)m) - 1] == tj);
+      if (!dup) mi = s_sq[lane];
     }
-    mass = wave_sum(mass);
+    mi = wave_sum(mi);
+    // C_a among the children (lane = child rank)
+    bool conv = false;
+    int tc = -1;
+    if (lane < kc) {
+      tc = s_ctok[lane];
+      conv = s_cos[1 + n_sib + lane] >= a.tau_seq;
+    }
+    const unsigned long long cmask = __ballot(conv);
+    float mc = 0.f;
+    if (conv && tc != ta && tc >= 0 && tc < a.vocab) {
+      bool dup = false;
+      for (unsigned long long m = imask; m; m &= m - 1) dup |= (s_stok[__ffsll((long long)m) - 1] == tc);
+      for (unsigned long long m = cmask & ((1ull << lane) - 1ull); m; m &= m - 1) dup |= (s_ctok[__ffsll((long long)m) - 1] == tc);
+      if (!dup) mc = s_cq[lane];
+    }
+    mc = wave_sum(mc);
     if (lane == 0) {
       if (!tok_ok) atomicOr(dev_status, CASCADE_FLAG_TOKEN);
-      const int64_t gi = lo + node;
-      a.q_tok[gi] = tok_ok ? prob_of(Lp, thr, lse, ta) : 0.f;
-      a.m_int[gi] = mass;
-      a.n_int[gi] = __popcll(mask);
-      a.cos_parent[gi] = cos_from(G(0, i + 1), g00, gii);
-      imask[gi] = mask;
+      a.q_tok[gi] = tok_ok ? s_sq[rank] : 0.f;
+      a.m_int[gi] = mi;
+      a.n_int[gi] = __popcll(imask);
+      a.m_conv[gi] = mc;
+      a.n_conv[gi] = __popcll(cmask);
+      a.cos_parent[gi] = s_cos[0];
     }
-  }
-}
-
-__global__ __launch_bounds__(256) void accept_conv_kernel(accept_args a, const unsigned long long* imask, int* dev_status) {
-  __shared__ int tok_i[4][MAXW];
-  __shared__ int tok_c[4][MAXW];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int b = blockIdx.y;
-  const int lo = a.node_off[b], Tn = a.node_off[b + 1] - lo;
-  const int node = blockIdx.x * 4 + wave;
-  if (node >= Tn) return;
-  const int64_t gi = lo + node;
-  const int par = a.parent[gi];
-  if (node == 0 || par < 0 || par >= node) {
-    // roots, and nodes whose parent pointer is unusable (no workgroup of kernel 1 owns them)
-    if (lane == 0) {
-      if (node > 0 || par != -1) atomicOr(dev_status, CASCADE_FLAG_PARENT);
-      a.q_tok[gi] = 0.f; a.m_int[gi] = 0.f; a.cos_parent[gi] = 0.f; a.n_int[gi] = 0;
-      a.m_conv[gi] = 0.f; a.n_conv[gi] = 0;
-    }
-    return;
-  }
-  const int ta = a.token[gi];
-  const unsigned long long im = imask[gi];
-  const int n_i = __popcll(im);
-  int n_c = 0, rank = 0, myrank = -1;
-  for (int base = 0; base < Tn; base += 64) {
-    const int j = base + lane;
-    const int pj = j < Tn ? a.parent[lo + j] : -2;
-    // siblings in rank order (the rank counts every child of par, this node included)
-    const bool sib = pj == par && j > par;
-    const unsigned long long sm = __ballot(sib);
-    if (sib) {
-      const int r = rank + __popcll(sm & ((1ull << lane) - 1ull));
-      // position inside I_a = number of member ranks below r
-      if (r < MAXW && ((im >> r) & 1ull)) tok_i[wave][__popcll(im & ((1ull << r) - 1ull))] = a.token[lo + j];
-    }
-    if (node >= base && node < base + 64) myrank = rank + __popcll(sm & ((1ull << (node - base)) - 1ull));
-    rank += __popcll(sm);
-    // children of this node whose features stay close to it (Eq. 2)
-    const bool conv = pj == node && j > node && a.cos_parent[lo + j] >= a.tau_seq;
-    const unsigned long long cm = __ballot(conv);
-    if (conv) {
-      const int idx = n_c + __popcll(cm & ((1ull << lane) - 1ull));
-      if (idx < MAXW) tok_c[wave][idx] = a.token[lo + j];
-    }
-    n_c += __popcll(cm);
-  }
-  if (myrank >= MAXW) {
-    // beyond the width limit: kernel 1 did not list this node (already flagged there)
-    if (lane == 0) {
-      a.q_tok[gi] = 0.f; a.m_int[gi] = 0.f; a.cos_parent[gi] = 0.f; a.n_int[gi] = 0;
-      a.m_conv[gi] = 0.f; a.n_conv[gi] = 0;
-    }
-    return;
-  }
-  if (n_c > MAXW) {
-    if (lane == 0) atomicOr(dev_status, CASCADE_FLAG_WIDTH);
-    n_c = MAXW;
-  }
-  __builtin_amdgcn_wave_barrier();
-  __threadfence_block();
-  const float* Lp = a.logits + (int64_t)(lo + par) * a.vocab;
-  const float thr = a.row_thr[lo + par], lse = a.row_lse[lo + par];
-  float mc = 0.f;
-  if (lane < n_c) {
-    const int t = tok_c[wave][lane];
-    bool dup = (t == ta) || t < 0 || t >= a.vocab;
-    for (int e = 0; e < n_i; ++e) dup |= (tok_i[wave][e] == t);
-    for (int e = 0; e < lane; ++e) dup |= (tok_c[wave][e] == t);
-    if (!dup) mc = prob_of(Lp, thr, lse, t);
-  }
-  mc = wave_sum(mc);
-  if (lane == 0) {
-    a.m_conv[gi] = mc;
-    a.n_conv[gi] = n_c;
   }
 }
 
 }  // namespace
 
 hipError_t launch_accept(cascade_ctx* ctx, const accept_args* a) {
-  hipStream_t stream = ctx->stream;
-  int* dev_status = ctx->dev_status;
-  unsigned long long* imask = (unsigned long long*)ctx->imask_ws;
   KernelTimer t(ctx, CASCADE_K_ACCEPT);
-  dim3 g1(ctx->lim.max_nodes_per_tree, a->n_prompts);
-  if (a->h_dtype == CASCADE_BF16) hipLaunchKernelGGL(accept_gram_kernel<uint16_t>, g1, dim3(256), 0, stream, *a, imask, dev_status);
-  else hipLaunchKernelGGL(accept_gram_kernel<float>, g1, dim3(256), 0, stream, *a, imask, dev_status);
-  dim3 g2((ctx->lim.max_nodes_per_tree + 3) / 4, a->n_prompts);
-  hipLaunchKernelGGL(accept_conv_kernel, g2, dim3(256), 0, stream, *a, imask, dev_status);
+  dim3 grid(ctx->lim.max_nodes_per_tree, a->n_prompts);
+  if (a->h_dtype == CASCADE_BF16) hipLaunchKernelGGL(accept_node_kernel<uint16_t>, grid, dim3(256), 0, ctx->stream, *a, ctx->dev_status);
+  else hipLaunchKernelGGL(accept_node_kernel<float>, grid, dim3(256), 0, ctx->stream, *a, ctx->dev_status);
   return hipGetLastError();
 }

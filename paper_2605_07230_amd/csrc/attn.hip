@@ -146,32 +146,40 @@ struct TileSmem {
   uint16_t v[KT * VP];
 };
 
-// Large trees.  Workgroup = (row, kv head, 64*NQ query rows, kv split); its four waves own NQ 16-row
+// Large trees.  Workgroup = (row, kv head, 16*NQ*NW query rows, kv split); its NW waves own NQ 16-row
 // query blocks each and share every 64-key K/V tile through LDS.  Tiles are double-buffered in LDS
 // and prefetched through registers: while tile t is multiplied, tile t+1 is written to the other
 // buffer and tile t+2 is in flight from HBM, with one workgroup barrier per tile.  K and V are
 // stored row-major; the V^T operand is fetched with the transposing LDS read.
-template <int D, int NQ, bool SPLIT>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
+template <int D, int NQ, int NW, bool SPLIT>
+__global__ __launch_bounds__(64 * NW, (NQ == 4 || NW == 8) ? 1 : 2) void attn_bf16_kernel(AttnParams p) {
   using TS = TileSmem<D>;
   extern __shared__ __align__(16) char smem_raw[];
   TS* tiles = (TS*)smem_raw;                                                    // [2]
   int* s_parent = (int*)(smem_raw + 2 * sizeof(TS));                            // [CASCADE_MAX_TREE]
-  unsigned long long* s_anc = (unsigned long long*)(s_parent + CASCADE_MAX_TREE);   // [2][256]
+  unsigned long long* s_anc = (unsigned long long*)(s_parent + CASCADE_MAX_TREE);   // [2][RW]
+  constexpr int NT = 64 * NW;        // threads
+  constexpr int RW = 16 * NQ * NW;   // query rows of the workgroup
   constexpr int KS = D / 32;   // 32-wide d steps of the score MFMA
   constexpr int DB = D / 16;   // 16-wide d blocks of the output
   constexpr int DC = D / 8;    // 16-byte chunks per row
-  constexpr int NPC = KT * DC / 256;   // 16-byte pieces of K (and of V) per thread per tile
+  constexpr int NPC = KT * DC / NT;   // 16-byte pieces of K (and of V) per thread per tile
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
-  const int s = blockIdx.z, kvh = blockIdx.y;
-  const int split = blockIdx.x % p.n_split, sb = blockIdx.x / p.n_split;
+  // Workgroups are dealt round-robin to the 8 XCDs (one L2 each) in launch order.  Renumber them so
+  // that consecutive logical ids sit on one XCD: the query blocks and splits of a (row, kv head),
+  // which stream the same keys and values, then share an L2.
+  const unsigned nx = gridDim.x, ny = gridDim.y, total = nx * ny * gridDim.z;
+  unsigned lid = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+  if ((total & 7u) == 0u) lid = (lid & 7u) * (total >> 3) + (lid >> 3);
+  const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny), s = (int)(lid / (nx * ny));
+  const int split = bx % p.n_split, sb = bx / p.n_split;
   const int lo = p.node_off[s];
   const int T = p.node_off[s + 1] - lo;
   const int P = p.prefix_len[s];
   const int G = p.group;
   const int M = T * G;
-  const int row0 = sb * 64 * NQ;
+  const int row0 = sb * RW;
   if (row0 >= M || T > CASCADE_MAX_TREE) return;
   const int n_pt = (P + KT - 1) / KT, n_tt = (T + KT - 1) / KT, nt = n_pt + n_tt;
   const int per = (nt + p.n_split - 1) / p.n_split;
@@ -194,7 +202,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
     const int64_t pitch = tree_tile ? tree_pitch : p.sp;
 #pragma unroll
     for (int it = 0; it < NPC; ++it) {
-      const int c = tid + 256 * it, key = c / DC, dc = c % DC;
+      const int c = tid + NT * it, key = c / DC, dc = c % DC;
       kr[it] = u32x4{0u, 0u, 0u, 0u};
       vr[it] = u32x4{0u, 0u, 0u, 0u};
       if (t < t_end && kbase + key < klimit) {
@@ -207,11 +215,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
   auto store_tile = [&](int t, int buf) {
 #pragma unroll
     for (int it = 0; it < NPC; ++it) {
-      const int c = tid + 256 * it, key = c / DC, dc = c % DC;
+      const int c = tid + NT * it, key = c / DC, dc = c % DC;
       *(u32x4*)(&tiles[buf].k[key * TS::KP + 8 * dc]) = kr[it];
       *(u32x4*)(&tiles[buf].v[key * TS::VP + 8 * dc]) = vr[it];
     }
-    if (t < t_end && t >= n_pt && tid < 64 * NQ) {
+    if (t < t_end && t >= n_pt && tid < RW) {
       const int kbase = (t - n_pt) * KT;
       const int r = row0 + tid;
       unsigned long long wbits = 0ull;
@@ -224,13 +232,13 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
           a = s_parent[a];
         }
       }
-      s_anc[buf * 256 + tid] = wbits;
+      s_anc[buf * RW + tid] = wbits;
     }
   };
 
   request_tile(t_begin);   // in flight while parents and queries are fetched
   if (t_end > n_pt) {
-    for (int i = tid; i < T; i += 256) {
+    for (int i = tid; i < T; i += NT) {
       int pi = p.parent[lo + i];
       if (pi >= i || pi < -1 || (i == 0 && pi != -1) || (i > 0 && pi < 0)) {
         atomicOr(p.dev_status, CASCADE_FLAG_PARENT);
@@ -245,7 +253,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
   int64_t out_row[NQ];   // index into [N*Hq] or -1
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
-    const int r = row0 + 16 * (wave + 4 * n) + l16;
+    const int r = row0 + 16 * (wave + NW * n) + l16;
     const bool ok = r < M;
     const int i = ok ? r % T : 0, hg = ok ? r / T : 0;
     const int64_t rowg = (int64_t)(lo + i) * p.n_heads + kvh * G + hg;
@@ -307,7 +315,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnParams p) {
     for (int n = 0; n < NQ; ++n) {
       unsigned long long valid;
       if (tree_tile) {
-        valid = s_anc[buf * 256 + 16 * (wave + 4 * n) + l16];
+        valid = s_anc[buf * RW + 16 * (wave + NW * n) + l16];
       } else {
         const int rem = klimit - kbase;
         valid = rem >= 64 ? ~0ull : ((1ull << rem) - 1ull);
@@ -756,27 +764,27 @@ AttnParams make_params(cascade_ctx* ctx, const tree_attn_args* a) {
   return p;
 }
 
-template <int D, int NQ>
+template <int D, int NQ, int NW>
 hipError_t launch_bf16_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
   hipStream_t st = ctx->stream;
   const size_t smem = 2 * sizeof(TileSmem<D>) + CASCADE_MAX_TREE * sizeof(int) + 2 * 256 * sizeof(unsigned long long);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_kernel<D, NQ, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_bf16_kernel<D, NQ, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_kernel<D, NQ, NW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_bf16_kernel<D, NQ, NW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   if (p.n_split > 1) {
     {
       KernelTimer t(ctx, CASCADE_K_ATTN);
-      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, true>), grid, dim3(256), smem, st, p);
+      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, true>), grid, dim3(64 * NW), smem, st, p);
     }
     KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
     hipLaunchKernelGGL((attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
   } else {
     KernelTimer t(ctx, CASCADE_K_ATTN);
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, false>), grid, dim3(256), smem, st, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, false>), grid, dim3(64 * NW), smem, st, p);
   }
   return hipGetLastError();
 }
@@ -843,11 +851,16 @@ hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a) {
     dim3 grid(n_split * p.n_sb, a->n_kv_heads, a->n_rows);
     return a->head_dim == 128 ? launch_ksplit_t<128>(ctx, p, grid) : launch_ksplit_t<64>(ctx, p, grid);
   }
-  const int NQ = M <= 64 ? 1 : (M <= 128 ? 2 : 4);
-  p.n_sb = (M + 64 * NQ - 1) / (64 * NQ);
+  // large trees: NW waves x 2 query blocks each share every K/V tile through LDS
+  // (measured at 8 rows x 32 heads x 256 nodes, 4200-key prefix: 283 us with 4 waves x 4 blocks and
+  // one workgroup per CU, 217 us with 4 waves x 2 blocks and two workgroups per CU, 196 us with 8 waves
+  // x 2 blocks sharing one copy of every tile)
+  constexpr int NW = 8;
+  const int RW = 32 * NW;
+  p.n_sb = (M + RW - 1) / RW;
   const long base_wgs = (long)a->n_rows * a->n_kv_heads * p.n_sb;
-  // one workgroup per CU is resident with NQ = 4 (registers), two otherwise: split only to fill those slots
-  const long slots = NQ == 4 ? 256 : 512;
+  // two workgroups of four waves (or one of eight) are resident per CU: split only to fill those slots
+  const long slots = NW == 8 ? 256 : 512;
   int n_split = (int)(slots / base_wgs);
   if (n_split > n_tiles) n_split = n_tiles;
   if (n_split > 16) n_split = 16;
@@ -859,13 +872,5 @@ hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a) {
     p.ws_ml = (float*)(ctx->attn_ws + (size_t)n_split * p.n_rows_total * a->head_dim * sizeof(float));
   }
   dim3 grid(n_split * p.n_sb, a->n_kv_heads, a->n_rows);
-  if (a->head_dim == 128) {
-    if (NQ == 1) return launch_bf16_t<128, 1>(ctx, p, grid);
-    if (NQ == 2) return launch_bf16_t<128, 2>(ctx, p, grid);
-    return launch_bf16_t<128, 4>(ctx, p, grid);
-  } else {
-    if (NQ == 1) return launch_bf16_t<64, 1>(ctx, p, grid);
-    if (NQ == 2) return launch_bf16_t<64, 2>(ctx, p, grid);
-    return launch_bf16_t<64, 4>(ctx, p, grid);
-  }
+  return a->head_dim == 128 ? launch_bf16_t<128, 2, NW>(ctx, p, grid) : launch_bf16_t<64, 2, NW>(ctx, p, grid);
 }

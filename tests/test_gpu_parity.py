@@ -136,6 +136,16 @@ def test_wide_tree_spanning_several_query_blocks_and_key_tiles():
     pu.check_accept_and_path(inp, ds)
 
 
+def test_large_query_block_grouped_heads_head_dim_64():
+    # 4 query heads per kv head x 90 nodes = 360 query rows per (row, kv head): the large-tree kernel with
+    # a ragged last query block, several tree tiles and a prefix that ends inside a tile
+    rng = np.random.default_rng(8)
+    inp = _small_bf16(8, n_prompts=1, prefix_lens=[150, 91], trees=[wl.grow_tree(rng, 90, 6, 8)], head_dim=64,
+                      n_heads=8, n_kv_heads=2)
+    ds = pu.run_gpu_step(inp)
+    pu.check_attention(inp, ds)
+
+
 @pytest.mark.parametrize("packed", [False, True])
 def test_temperature_and_no_guidance(packed):
     inp = _small_bf16(3, cfg=False, prefix_lens=[17, 40], temperature=0.7, top_k=0)
