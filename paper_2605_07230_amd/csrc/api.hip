@@ -63,14 +63,12 @@ int cascade_create(cascade_ctx** out, const cascade_limits* lim, void* hip_strea
   c->attn_ws_bytes = align_up(attn, 256);
   // packed hidden states: two operands (cond, uncond), rows rounded up to 256, 2 bytes per element
   c->hpack_ws_bytes = align_up((size_t)2 * ((lim->max_nodes_total + 255) / 256 * 256) * lim->hidden * 2, 256);
-  const size_t imask_bytes = align_up((size_t)lim->max_nodes_total * 8, 256);
-  c->ws_bytes = 256 + c->attn_ws_bytes + c->hpack_ws_bytes + imask_bytes;
+  c->ws_bytes = 256 + c->attn_ws_bytes + c->hpack_ws_bytes;
   e = hipMalloc((void**)&c->ws, c->ws_bytes);
   if (e != hipSuccess) { delete c; (void)hipGetLastError(); return CASCADE_ENOMEM; }
   c->dev_status = (int*)c->ws;
   c->attn_ws = c->ws + 256;
   c->hpack_ws = c->attn_ws + c->attn_ws_bytes;
-  c->imask_ws = c->hpack_ws + c->hpack_ws_bytes;
   e = hipMemsetAsync(c->ws, 0, 256, c->stream);
   if (e != hipSuccess) { (void)hipFree(c->ws); delete c; return hip_fail(e); }
   *out = c;

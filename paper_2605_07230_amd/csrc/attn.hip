@@ -707,6 +707,255 @@ __global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams 
   }
 }
 
+// ---------------------------------------------------------------------- bf16, few query rows
+// When a step has so few (row, kv head, 64-query block) units that they cannot fill the GPU, the
+// query rows are split instead of the keys: workgroup = (row, kv head, 16 query rows), eight
+// waves, wave w owning the 64-key tiles w, w + 8, ... of the whole key range.  A wave keeps its
+// tile to itself: K is loaded from global memory directly in MFMA operand order (16-byte pieces of
+// one key row per lane), V goes through a wave-private LDS region only to be read back transposed.
+// No workgroup barrier inside the tile loop; the eight (m, l, O) partials are merged through LDS at
+// the end.  Keys and values are read by every query block of a (row, kv head) - from L2.
+template <int D>
+__global__ __launch_bounds__(512) void attn_bf16_qsplit_kernel(AttnParams p) {
+  constexpr int NWV = 8, NT = 512;
+  constexpr int KS = D / 32, DB = D / 16, DC = D / 8;
+  constexpr int VP = D + 16;           // V row pitch (elements), as in the other kernels
+  constexpr int OP = D + 4;            // merge buffer row pitch (floats)
+  constexpr int NVC = KT * DC / 64;    // 16-byte pieces of V per lane per tile
+  extern __shared__ __align__(16) char smem_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  uint16_t* vt = (uint16_t*)smem_raw + (size_t)wave * KT * VP;                         // this wave's V tile
+  int* s_parent = (int*)(smem_raw + (size_t)NWV * KT * VP * sizeof(uint16_t));         // [128]
+  unsigned long long* s_anc = (unsigned long long*)(s_parent + 128);                   // [2 tree tiles][16 rows]
+
+  // consecutive logical ids on one XCD (see the large-tree kernel): the query blocks of a (row, kv head) share an L2
+  const unsigned nx = gridDim.x, ny = gridDim.y, total = nx * ny * gridDim.z;
+  unsigned lid = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+  if ((total & 7u) == 0u) lid = (lid & 7u) * (total >> 3) + (lid >> 3);
+  const int sb = (int)(lid % nx), kvh = (int)((lid / nx) % ny), s = (int)(lid / (nx * ny));
+  const int lo = p.node_off[s];
+  const int T = p.node_off[s + 1] - lo;
+  const int P = p.prefix_len[s];
+  const int G = p.group;
+  const int M = T * G;
+  const int row0 = sb * 16;
+  if (row0 >= M || T > 128) return;
+  const int n_pt = (P + KT - 1) / KT, n_tt = (T + KT - 1) / KT, nt = n_pt + n_tt;
+
+  const uint16_t* kc = (const uint16_t*)p.k_cache + s * p.sr + kvh * p.sh;
+  const uint16_t* vc = (const uint16_t*)p.v_cache + s * p.sr + kvh * p.sh;
+  const uint16_t* ktr = (const uint16_t*)p.k_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D;
+  const uint16_t* vtr = (const uint16_t*)p.v_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D;
+  const int64_t tree_pitch = (int64_t)p.n_kv_heads * D;
+
+  // tile registers: K fragments kf[kt][ks] = key 16 kt + l16, d 32 ks + 8 g .. + 7 ; V pieces c = lane + 64 it
+  u32x4 kf[4][KS], vr[NVC];
+  auto request_tile = [&](int t) {
+    const bool tree_tile = t >= n_pt;
+    const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
+    const int klimit = tree_tile ? T : P;
+    const uint16_t* ksrc = tree_tile ? ktr : kc;
+    const uint16_t* vsrc = tree_tile ? vtr : vc;
+    const int64_t pitch = tree_tile ? tree_pitch : p.sp;
+    const int last = max(klimit - 1, 0);   // clamped row for loads past the end (zeroed below)
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      const int key = kbase + 16 * kt + l16;
+      const uint16_t* kp = ksrc + (int64_t)min(key, last) * pitch + 8 * g;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const u32x4 x = *(const u32x4*)(kp + 32 * ks);
+        kf[kt][ks] = (t < nt && key < klimit) ? x : u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < NVC; ++it) {
+      const int c = lane + 64 * it, key = kbase + c / DC, dc = c % DC;
+      const u32x4 x = *(const u32x4*)(vsrc + (int64_t)min(key, last) * pitch + 8 * dc);
+      vr[it] = (t < nt && key < klimit) ? x : u32x4{0u, 0u, 0u, 0u};
+    }
+  };
+  const bool has_keys = P > 0 || T > 0;   // T >= 1 for a row that reaches this point
+  if (wave < nt && has_keys) request_tile(wave);
+
+  for (int i = tid; i < T; i += NT) {
+    int pi = p.parent[lo + i];
+    if (pi >= i || pi < -1 || (i == 0 && pi != -1) || (i > 0 && pi < 0)) {
+      atomicOr(p.dev_status, CASCADE_FLAG_PARENT);
+      pi = (i == 0) ? -1 : 0;
+    }
+    s_parent[i] = pi;
+  }
+
+  // the workgroup's 16 query rows (B operand of S^T): lane = (query l16, d group g)
+  Frag8 qf[KS];
+  const int qr = row0 + l16;
+  const bool q_ok = qr < M;
+  const int qi = q_ok ? qr % T : 0, qh = q_ok ? qr / T : 0;
+  const int64_t rowg = (int64_t)(lo + qi) * p.n_heads + kvh * G + qh;
+  {
+    const uint16_t* qp = (const uint16_t*)p.q + rowg * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (q_ok) qf[ks].u = *(const uint4*)(qp + 32 * ks);
+      else qf[ks].u = make_uint4(0, 0, 0, 0);
+    }
+  }
+  __syncthreads();   // parent array complete
+  if (tid < 32) {
+    // ancestor-or-self bits of the (at most two) tree tiles for the 16 query rows
+    const int tt = tid >> 4, rr = row0 + (tid & 15), kbase = tt * KT;
+    unsigned long long wbits = 0ull;
+    if (rr < M && tt < n_tt) {
+      int a = rr % T, guard = 0;
+      while (a >= 0 && guard++ <= 128) {
+        const int rel = a - kbase;
+        if (rel < 0) break;
+        if (rel < 64) wbits |= 1ull << rel;
+        a = s_parent[a];
+      }
+    }
+    s_anc[tid] = wbits;
+  }
+  __syncthreads();
+
+  f32x4 ot[DB];
+  float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+  for (int db = 0; db < DB; ++db) ot[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int t = wave; t < nt; t += NWV) {
+    const bool tree_tile = t >= n_pt;
+    const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
+    const int klimit = tree_tile ? T : P;
+    // V: registers -> this wave's LDS tile (row-major); the previous tile's reads are complete (same wave, in order)
+#pragma unroll
+    for (int it = 0; it < NVC; ++it) {
+      const int c = lane + 64 * it;
+      *(u32x4*)(&vt[(c / DC) * VP + 8 * (c % DC)]) = vr[it];
+    }
+    __builtin_amdgcn_wave_barrier();   // keep the tile's stores ahead of its transposing reads in program order
+    // S^T = K Q^T from the register fragments
+    f32x4 st[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      st[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        Frag8 a8;
+        a8.u = make_uint4(kf[kt][ks][0], kf[kt][ks][1], kf[kt][ks][2], kf[kt][ks][3]);
+        st[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8.v, qf[ks].v, st[kt], 0, 0, 0);
+      }
+    }
+    if (t + NWV < nt) request_tile(t + NWV);   // next tile of this wave streams in during the softmax
+
+    unsigned long long valid;
+    if (tree_tile) {
+      valid = s_anc[16 * (t - n_pt) + l16];
+    } else {
+      const int rem = klimit - kbase;
+      valid = rem >= 64 ? ~0ull : ((1ull << rem) - 1ull);
+    }
+    if (!q_ok) valid = 0ull;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      const uint32_t nib = (uint32_t)(valid >> (16 * kt + 4 * g));   // this lane's 4 keys of sub-tile kt
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float z = ((nib >> c) & 1u) ? st[kt][c] * p.scale_log2e : -INFINITY;
+        st[kt][c] = z;
+        mx = fmaxf(mx, z);
+      }
+    }
+    mx = rows4_max(mx);
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2(m_run - m_use);
+    float ls = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float e = fast_exp2(st[kt][c] - m_use);
+        st[kt][c] = e;
+        ls += e;
+      }
+    l_run = l_run * alpha + ls;
+    m_run = m_new;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) ot[db] *= alpha;
+    Frag8 pf[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      pf[j].u.x = pack_bf16x2(st[2 * j][0], st[2 * j][1]);
+      pf[j].u.y = pack_bf16x2(st[2 * j][2], st[2 * j][3]);
+      pf[j].u.z = pack_bf16x2(st[2 * j + 1][0], st[2 * j + 1][1]);
+      pf[j].u.w = pack_bf16x2(st[2 * j + 1][2], st[2 * j + 1][3]);
+    }
+    // O^T += V^T P^T with transposing reads of the wave's V tile (LDS operations of one wave complete in order)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const uint16_t* vp = &vt[(32 * j + 4 * g + (l16 >> 2)) * VP + 16 * db + 4 * (l16 & 3)];
+        union { Frag8 f; s16x4 h[2]; } vf;
+        vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp));
+        vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp + 16 * VP));
+        ot[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.f.v, pf[j].v, ot[db], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();   // and the reads ahead of the next tile's stores
+  }
+
+  // merge the eight waves' partials through LDS (the V tiles are reused)
+  l_run = rows4_sum(l_run);
+  __syncthreads();
+  float* mo = (float*)smem_raw;                 // [NWV][16 rows][OP]
+  float* mml = mo + NWV * 16 * OP;              // [NWV][16 rows][2]
+  {
+    float* orow = mo + (wave * 16 + l16) * OP;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) *(f32x4*)(orow + 16 * db + 4 * g) = ot[db];
+    if (g == 0) {
+      mml[(wave * 16 + l16) * 2] = m_run;
+      mml[(wave * 16 + l16) * 2 + 1] = l_run;
+    }
+  }
+  __syncthreads();
+  {
+    constexpr int TPR = NT / 16;                 // threads per output row
+    constexpr int DQ = D / TPR;                  // d range of one thread (4 for D = 128, 2 for D = 64)
+    const int row = tid / TPR, dq = tid % TPR;
+    const int rr = row0 + row;
+    if (rr < M) {
+      float mw[NWV], m = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) { mw[w] = mml[(w * 16 + row) * 2]; m = fmaxf(m, mw[w]); }
+      float l = 0.f, o[DQ];
+#pragma unroll
+      for (int d = 0; d < DQ; ++d) o[d] = 0.f;
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) {
+        if (mw[w] == -INFINITY) continue;
+        const float sc = fast_exp2(mw[w] - m);
+        l += sc * mml[(w * 16 + row) * 2 + 1];
+        const float* orow = mo + (w * 16 + row) * OP + DQ * dq;
+#pragma unroll
+        for (int d = 0; d < DQ; ++d) o[d] += sc * orow[d];
+      }
+      const int i = rr % T, hg = rr / T;
+      const int64_t rg = (int64_t)(lo + i) * p.n_heads + kvh * G + hg;
+      const float inv = 1.f / l;
+      uint16_t* op = (uint16_t*)p.out + rg * D + DQ * dq;
+#pragma unroll
+      for (int d = 0; d < DQ; d += 2) *(uint32_t*)(op + d) = pack_bf16x2(o[d] * inv, o[d + 1] * inv);
+      if (dq == 0 && p.lse) p.lse[rg] = m * LN2 + logf(l);
+    }
+  }
+}
+
 // log-sum-exp merge of the split partials: D/4 lanes per output row (a float4 each), 256 threads
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnParams p) {
@@ -827,11 +1076,33 @@ hipError_t launch_ksplit_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
   return hipGetLastError();
 }
 
+template <int D>
+hipError_t launch_qsplit_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
+  constexpr int VP = D + 16;
+  const size_t smem = (size_t)8 * KT * VP * sizeof(uint16_t) + 128 * sizeof(int) + 32 * sizeof(unsigned long long);
+  static_assert(8 * 16 * (D + 4) * 4 + 8 * 16 * 2 * 4 <= 8 * KT * (D + 16) * 2, "merge buffers fit in the V tiles");
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_qsplit_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  KernelTimer t(ctx, CASCADE_K_ATTN);
+  hipLaunchKernelGGL((attn_bf16_qsplit_kernel<D>), grid, dim3(512), smem, ctx->stream, p);
+  return hipGetLastError();
+}
+
 hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a) {
   AttnParams p = make_params(ctx, a);
   const int M = a->max_nodes_per_tree * p.group;   // query rows per (row, kv head)
   const int n_tiles = (a->max_prefix_len + KT - 1) / KT + (a->max_nodes_per_tree + KT - 1) / KT;
   const size_t per_split = (size_t)p.n_rows_total * (a->head_dim + 2) * sizeof(float);
+  if (M <= 128 && (long)a->n_rows * a->n_kv_heads * ((M + 63) / 64) <= 128 && a->max_nodes_per_tree <= 128) {
+    // too few 64-row units to fill the GPU: split the query rows, not the keys (no partials, no merge kernel)
+    p.n_sb = (M + 15) / 16;
+    dim3 grid(p.n_sb, a->n_kv_heads, a->n_rows);
+    return a->head_dim == 128 ? launch_qsplit_t<128>(ctx, p, grid) : launch_qsplit_t<64>(ctx, p, grid);
+  }
   if (M <= 128) {
     // small trees: key groups split the tiles inside the workgroup; split across workgroups only when a
     // workgroup would otherwise walk more than 16 tiles (4 rounds) and the GPU is not yet full

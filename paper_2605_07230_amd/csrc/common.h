@@ -19,7 +19,6 @@ struct cascade_ctx {
   size_t attn_ws_bytes;
   char* hpack_ws;         // hidden states repacked into MFMA operand order, cond then uncond
   size_t hpack_ws_bytes;
-  char* imask_ws;         // one 64-bit interchangeable-set mask per node (cascade_accept, kernel 1 -> kernel 2)
   // optional per-kernel timing with HIP events on the ctx stream (cascade_set_kernel_timing)
   bool timing;
   hipEvent_t* ev;         // [CASCADE_K_COUNT][TIMING_RING][2], created on first enable
