@@ -74,6 +74,51 @@ def cpu_baseline(inp, budget_s: float = 12.0):
             "sample": f"{n} whole step(s) of the same workload (numpy float64; BLAS threads = cores), {el:.1f} s"}
 
 
+def tau_sweep(args) -> int:
+    """Stress-shaped trees over many seeds: mean accepted length and acceptance / walk time per
+    threshold (both thresholds set to tau).  One LM-head matrix is shared by all seeds and the
+    prefix is cut to 64 tokens (attention does not depend on the thresholds)."""
+    import numpy as np
+    import torch
+    from paper_2605_07230_amd import binding, workloads as wl
+    binding.load_library()
+    taus = (0.8, 0.9, 0.95)
+    acc_len = {t: [] for t in taus}
+    acc_us = {t: [] for t in taus}
+    sel_us = {t: [] for t in taus}
+    w0, w_packed = None, None
+    for seed in range(args.sweep_seeds):
+        inp = wl.make_config(4, seed, prefix_lens=[64] * 8, w=w0)
+        if w0 is None:
+            w0 = inp.w
+        ds = binding.DeviceStep(inp)
+        if w_packed is None:
+            w_packed = ds.pack_w()
+        ds.lmhead(w_packed, binding.W_PACKED32)
+        for t in taus:
+            for rep in range(3):
+                ds.accept(t, t)
+                ds.select()
+            ds.ctx.set_kernel_timing(True)
+            for rep in range(10):
+                ds.accept(t, t)
+                ds.select()
+            ms_a, n_a = ds.ctx.read_kernel_timing(4)
+            ms_s, n_s = ds.ctx.read_kernel_timing(5)
+            ds.ctx.set_kernel_timing(False)
+            acc_len[t] += ds.accept_len.cpu().tolist()
+            acc_us[t].append(ms_a * 1e3 / n_a)
+            sel_us[t].append(ms_s * 1e3 / n_s)
+        assert ds.ctx.device_status() == binding.OK
+        ds.w = None
+        del ds
+    out = {"metric": "tau_sweep", "workload": "stress_1024px trees (prefix cut to 64), seeds 0..%d" % (args.sweep_seeds - 1),
+           "per_tau": {str(t): {"mean_accept_len": float(np.mean(acc_len[t])), "accept_us": float(np.mean(acc_us[t])),
+                                "select_us": float(np.mean(sel_us[t])), "prompts": len(acc_len[t])} for t in taus}}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,11 +132,15 @@ def main() -> int:
     ap.add_argument("--commit-layers", type=int, default=30, help="decoder layers in the separately timed KV commit (0: skip)")
     ap.add_argument("--weights-seqs", type=int, default=8, help="sequences in the separately timed Eq. 4 weight mask (0: skip)")
     ap.add_argument("--decode-image", type=int, default=0, help="tokens of the separately timed multi-step decode loop (0: skip)")
+    ap.add_argument("--tau-sweep", action="store_true", help="instead of the step benchmark: threshold sweep on stress-shaped trees")
+    ap.add_argument("--sweep-seeds", type=int, default=32)
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
         return 2
+    if args.tau_sweep:
+        return tau_sweep(args)
 
     import torch
     from paper_2605_07230_amd import binding, workloads as wl

@@ -200,13 +200,15 @@ def make_inputs(
     p_dup_sibling: float = 0.3,
     align: float = 1.5,
     regular_dups: bool = False,
+    w: Optional[np.ndarray] = None,
 ) -> VerifyInputs:
     """Draw one step's arrays.  See the module docstring for conventions.
 
     ``align`` scales a drafter/target alignment term: the conditional hidden state of a
     node is nudged towards the LM-head rows of its children's draft tokens, the way a
     trained drafter proposes tokens the target finds likely.  Without it a random LM head
-    accepts nothing and the walk would never leave the root.
+    accepts nothing and the walk would never leave the root.  ``w`` hands in an LM-head matrix
+    instead of drawing one.
     """
     rng = np.random.default_rng(seed)
     rows_per_prompt = 2 if cfg else 1
@@ -229,8 +231,12 @@ def make_inputs(
     row_parent = np.concatenate(row_parent_parts).astype(np.int32)
     N_a = int(row_node_off[-1])
 
-    # LM head
-    w = rnd(np.float32(0.02) * _randn(rng, (vocab, hidden)))
+    # LM head (a caller sweeping seeds may hand in one matrix to share; the other draws then come
+    # from a stream without the matrix's numbers in it)
+    if w is None:
+        w = rnd(np.float32(0.02) * _randn(rng, (vocab, hidden)))
+    else:
+        assert w.shape == (vocab, hidden)
 
     # draft tokens and the drafter's probability of each
     token = np.zeros(N_c, dtype=np.int32)
