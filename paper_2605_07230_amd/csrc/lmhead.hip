@@ -309,125 +309,6 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
   }
 }
 
-// Eight-wave variant for hidden size 4096: two waves per SIMD (<= 256 registers each), the eight
-// waves split the hidden dimension into 512-wide parts.  A single wave cannot keep the L2 -> CU
-// path busy (measured: 62 GB/s per CU with four waves, 93 GB/s with eight), and the conditional /
-// unconditional hidden states that every workgroup re-reads from L2 are 2/3 of its traffic.
-// Shallower request rings than the four-wave kernel (W 4 steps ahead, H 2), since two waves per
-// SIMD hide each other's waits.  Partial tiles are summed through LDS in two rounds.
-template <bool CFG>
-__global__ __launch_bounds__(512) void lmhead_bf16_packed8_kernel(LmParams p) {
-  constexpr int NA = CFG ? 4 : 2;
-  constexpr int NACC = NA * 2;
-  constexpr int NSTEPS = 32, HD = 2, WD = 4;
-  extern __shared__ float red[];    // [4 waves][NACC][16 regs][64 lanes]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r32 = lane & 31, half = lane >> 5;
-  constexpr int KS = 256;           // k16 steps in the hidden dimension (4096 / 16)
-
-  int logical = blockIdx.x;
-  const int nwg = gridDim.x;
-  if ((nwg & 7) == 0) logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
-  const int ntile = logical / p.n_mchunks, mc = logical % p.n_mchunks;
-  const int v0 = ntile * 64, node0 = mc * 64;
-
-  const uint4* ap[NA];
-#pragma unroll
-  for (int i = 0; i < NA; ++i) {
-    const uint4* base = (i < 2) ? p.hp_cond : p.hp_uncond;
-    ap[i] = base + ((int64_t)(mc * 2 + (i & 1)) * KS) * 64 + lane;
-  }
-  const uint4* bp[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) bp[j] = (const uint4*)p.w + ((int64_t)(ntile * 2 + j) * KS) * 64 + lane;
-
-  f32x16 acc[NA][2];
-#pragma unroll
-  for (int i = 0; i < NA; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  // this wave's k16 steps: 128-wide slices wave, wave + 8, wave + 16, wave + 24
-  auto ks_of_step = [&](int t) { return (wave + 8 * (t >> 3)) * 8 + (t & 7); };
-  Frag8 hr[HD][NA];
-  Frag8 wr[WD][2];
-  auto load_h = [&](int slot, int t) {
-    const int64_t o = (int64_t)ks_of_step(t) * 64;
-#pragma unroll
-    for (int i = 0; i < NA; ++i) hr[slot][i].u = ap[i][o];
-  };
-  auto load_w = [&](int slot, int t) {
-    const int64_t o = (int64_t)ks_of_step(t) * 64;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) wr[slot][j].u = bp[j][o];
-  };
-  // prologue in steady-state request order (..., H(t+HD), W(t+WD), ...)
-#pragma unroll
-  for (int t = 0; t < WD - HD; ++t) load_w(t, t);
-#pragma unroll
-  for (int t = 0; t < HD; ++t) {
-    load_h(t, t);
-    load_w(WD - HD + t, WD - HD + t);
-  }
-#pragma unroll
-  for (int t = 0; t < NSTEPS; ++t) {
-#pragma unroll
-    for (int i = 0; i < NA; ++i)
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
-        acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hr[t % HD][i].v, wr[t % WD][jj].v, acc[i][jj], 0, 0, 0);
-    if (t + HD < NSTEPS) load_h(t % HD, t + HD);
-    if (t + WD < NSTEPS) load_w(t % WD, t + WD);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-
-  // round 1: waves 4..7 hand their partial tiles to waves 0..3
-  if (wave >= 4) {
-#pragma unroll
-    for (int i = 0; i < NA; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) red[(((wave - 4) * NACC + i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
-  }
-  __syncthreads();
-  if (wave < 4) {
-#pragma unroll
-    for (int i = 0; i < NA; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] += red[((wave * NACC + i * 2 + j) * 16 + r) * 64 + lane];
-  }
-  __syncthreads();
-  // round 2: waves 0..3 publish, then each of the eight waves finishes half of one 32 x 32 output tile
-  if (wave < 4) {
-#pragma unroll
-    for (int i = 0; i < NA; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) red[((wave * NACC + i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
-  }
-  __syncthreads();
-  const int tile = wave >> 1, rhalf = wave & 1;   // tile = (node block, column block)
-  const int nbk = tile >> 1, nb = tile & 1;
-#pragma unroll
-  for (int rr = 0; rr < 8; ++rr) {
-    const int r = rhalf * 8 + rr;
-    float c = 0.f, u = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      c += red[((w * NACC + nbk * 2 + nb) * 16 + r) * 64 + lane];
-      if (CFG) u += red[((w * NACC + (2 + nbk) * 2 + nb) * 16 + r) * 64 + lane];
-    }
-    const float gmix = CFG ? u + p.cfg_scale * (c - u) : c;
-    const int node = node0 + 32 * nbk + 8 * (r >> 2) + 4 * half + (r & 3);
-    if (node < p.n_nodes) p.logits[(int64_t)node * p.vocab + v0 + 32 * nb + r32] = gmix / p.temperature;
-  }
-}
 
 // ------------------------------------------------------------------- bf16, packed, many rows
 // LDS-tiled projection for steps with several hundred rows (batched prompts), where the kernel is
@@ -703,11 +584,10 @@ hipError_t launch_lmhead_f32(cascade_ctx* ctx, const lmhead_args* a) {
   return hipGetLastError();
 }
 
-template <bool CFG, int KIND>   // KIND 0: row-major W, 1: packed, 2: packed + deep pipeline (4 waves), 3: packed, 8 waves
+template <bool CFG, int KIND>   // KIND 0: row-major W, 1: packed, 2: packed + deep pipeline
 hipError_t launch_bf16_gemm(cascade_ctx* ctx, const LmParams& p, int grid) {
   const size_t smem = (size_t)4 * (CFG ? 8 : 4) * 16 * 64 * sizeof(float);
-  auto kern = KIND == 3 ? lmhead_bf16_packed8_kernel<CFG>
-                        : (KIND == 2 ? lmhead_bf16_packed_kernel<CFG, 64> : (KIND == 1 ? lmhead_bf16_packed_kernel<CFG, 0> : lmhead_bf16_kernel<CFG>));
+  auto kern = KIND == 2 ? lmhead_bf16_packed_kernel<CFG, 64> : (KIND == 1 ? lmhead_bf16_packed_kernel<CFG, 0> : lmhead_bf16_kernel<CFG>);
   static bool attr_done = false;   // one flag per template instance
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -715,7 +595,7 @@ hipError_t launch_bf16_gemm(cascade_ctx* ctx, const LmParams& p, int grid) {
     attr_done = true;
   }
   KernelTimer t(ctx, CASCADE_K_LMHEAD);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(KIND == 3 ? 512 : 256), smem, ctx->stream, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, ctx->stream, p);
   return hipGetLastError();
 }
 

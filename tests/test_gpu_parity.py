@@ -175,6 +175,19 @@ def test_rows_with_all_equal_logits_take_the_wide_bin_path():
     pu.check_accept_and_path(inp, ds, require_margin=False)
 
 
+def test_rows_with_outliers():
+    # 40 vocabulary rows scaled by 60 give every logits row a few huge entries of either sign, far from
+    # the bulk: the k-th largest then sits many histogram bins below the row maximum
+    inp = _small_bf16(9, n_prompts=1, prefix_lens=[8, 8], trees=[wl.grow_tree(np.random.default_rng(9), 20, 3, 4)],
+                      hidden=128, vocab=8192, top_k=300, align=0.0)
+    inp.w[:40] = wl.round_bf16(inp.w[:40] * 60.0)
+    ds = pu.run_gpu_step(inp)
+    pu.check_lmhead(inp, ds)
+    g = ds.logits.cpu().numpy()
+    kept = (g >= ds.row_thr.cpu().numpy()[:, None]).sum(axis=1)
+    assert (kept >= 300).all() and (kept <= 310).all()
+
+
 def test_f32_ragged_batch():
     rng = np.random.default_rng(4)
     inp = _small_bf16(4, dtype="f32", head_dim=32, hidden=96, vocab=300, top_k=20,
