@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the read counter sees half of the bytes that 16-byte-per-lane loads move (factor 2.0), writes
 # count 1.0.  The summaries are profiles/*_pmc.md; None where no counter run exists.
 MEASURED_TRAFFIC_BYTES = {
-    ("janus_pro_7b", "lmhead"): int((69764.5 * 2.0 + 3840.0) * 1024),
+    ("janus_pro_7b", "lmhead"): int((69763.0 * 2.0 + 3840.0) * 1024),
 }
 
 
@@ -293,14 +293,16 @@ def main() -> int:
         else:
             nbytes = algorithmic_bytes_lmhead(inp)
             ach = nbytes / (kernel_us["lmhead"] * 1e-6) / 1e9
-            roof = {"kernel": "lmhead_bf16_packed_kernel" if packed else "lmhead_bf16_kernel", "bound": "hbm", "achieved": ach,
+            kname = "lmhead_f32_kernel" if inp.dtype == "f32" else ("lmhead_bf16_packed_kernel" if packed else "lmhead_bf16_kernel")
+            roof = {"kernel": kname, "bound": "hbm", "achieved": ach,
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
                     "algorithmic_bytes": nbytes, "frac_of_measured_peak": ach / hbm_meas}
     else:
         nbytes = algorithmic_bytes_attn(inp)
         us = kernel_us.get("attn", 0.0) + kernel_us.get("attn_merge", 0.0)
         ach = nbytes / (us * 1e-6) / 1e9
-        roof = {"kernel": "attn_bf16_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        roof = {"kernel": "attn_f32_kernel" if inp.dtype == "f32" else "attn_bf16_*_kernel", "bound": "hbm", "achieved": ach,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes": nbytes,
                 "frac_of_measured_peak": ach / hbm_meas}
     roof["avg_launch_us"] = kernel_us[dominant if dominant != "attn_merge" else "attn"]
