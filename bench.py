@@ -95,6 +95,33 @@ def tau_sweep(args) -> int:
         if w_packed is None:
             w_packed = ds.pack_w()
         ds.lmhead(w_packed, binding.W_PACKED32)
+        if args.rank_zipf:
+            # draft tokens re-drawn by rank: a child's token is the vocabulary entry at a Zipf(1.1)-distributed
+            # rank of its parent's mixed logits (measurement input only; torch sorts the library's logits)
+            rng = np.random.default_rng(seed + 99)
+            order = torch.argsort(ds.logits, dim=1, descending=True)
+            ranks_pmf = np.arange(1, inp.vocab + 1, dtype=np.float64) ** -1.1
+            ranks_pmf /= ranks_pmf.sum()
+            cdf = np.cumsum(ranks_pmf)
+            tok = inp.token.copy()
+            dprob = inp.draft_prob.copy()
+            for b in range(inp.n_prompts):
+                lo, hi = int(inp.node_off[b]), int(inp.node_off[b + 1])
+                par = inp.parent[lo:hi]
+                for p_ in range(hi - lo):
+                    kids = np.nonzero(par == p_)[0]
+                    if len(kids) == 0:
+                        continue
+                    chosen = []
+                    while len(chosen) < len(kids):            # distinct ranks among siblings
+                        r = int(np.searchsorted(cdf, rng.random()))
+                        if r not in chosen:
+                            chosen.append(min(r, inp.vocab - 1))
+                    ids = order[lo + p_, torch.tensor(chosen, device=order.device)].cpu().numpy()
+                    tok[lo + kids] = ids
+                    dprob[lo + kids] = ranks_pmf[chosen].astype(np.float32)
+            ds.token = torch.from_numpy(tok).to(ds.logits.device)
+            ds.draft_prob = torch.from_numpy(dprob).to(ds.logits.device)
         for t in taus:
             for rep in range(3):
                 ds.accept(t, t)
@@ -112,7 +139,8 @@ def tau_sweep(args) -> int:
         assert ds.ctx.device_status() == binding.OK
         ds.w = None
         del ds
-    out = {"metric": "tau_sweep", "workload": "stress_1024px trees (prefix cut to 64), seeds 0..%d" % (args.sweep_seeds - 1),
+    out = {"metric": "tau_sweep", "tokens": "rank-zipf of the parent's logits" if args.rank_zipf else "generator's tokens",
+           "workload": "stress_1024px trees (prefix cut to 64), seeds 0..%d" % (args.sweep_seeds - 1),
            "per_tau": {str(t): {"mean_accept_len": float(np.mean(acc_len[t])), "accept_us": float(np.mean(acc_us[t])),
                                 "select_us": float(np.mean(sel_us[t])), "prompts": len(acc_len[t])} for t in taus}}
     print(json.dumps(out))
@@ -134,6 +162,7 @@ def main() -> int:
     ap.add_argument("--decode-image", type=int, default=0, help="tokens of the separately timed multi-step decode loop (0: skip)")
     ap.add_argument("--tau-sweep", action="store_true", help="instead of the step benchmark: threshold sweep on stress-shaped trees")
     ap.add_argument("--sweep-seeds", type=int, default=32)
+    ap.add_argument("--rank-zipf", action="store_true", help="tau sweep: re-draw draft tokens by Zipf rank of the parent's logits")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
