@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
   __shared__ float s_cos[MAXO];         // cos(a, other)
   __shared__ int s_other[MAXO];         // node index of every other row: parent, siblings (without a), children
   __shared__ int s_stok[MAXW], s_ctok[MAXW];   // tokens of the siblings (by rank, a included) and of the children
-  __shared__ int s_chl[MAXW];                  // the children's node indices
+  __shared__ int s_sib[MAXW], s_chl[MAXW];     // node indices of the siblings (by rank, a included) and of the children
   __shared__ float s_sq[MAXW], s_cq[MAXW];     // their probabilities under the parent's distribution
   __shared__ int s_ks, s_kc, s_rank;
   __shared__ float s_aa;                       // |a|^2 (generic path)
@@ -148,9 +148,7 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
       if (sib) {
         const int r = ks + __popcll(sm & ((1ull << lane) - 1ull));
         if (r < MAXW) {
-          const int t = a.token[lo + j];
-          s_stok[r] = t;
-          s_sq[r] = (t >= 0 && t < a.vocab) ? prob_of(Lp, thr, lse, t) : 0.f;
+          s_sib[r] = j;
           // other index: parent is 0; siblings keep their rank order with a left out
           if (j != node) s_other[1 + r - (j > node ? 1 : 0)] = j;
         }
@@ -161,12 +159,7 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
       const unsigned long long cm = __ballot(ch);
       if (ch) {
         const int r = kc + __popcll(cm & ((1ull << lane) - 1ull));
-        if (r < MAXW) {
-          const int t = a.token[lo + j];
-          s_ctok[r] = t;
-          s_cq[r] = (t >= 0 && t < a.vocab) ? prob_of(Lp, thr, lse, t) : 0.f;
-          s_chl[r] = j;
-        }
+        if (r < MAXW) s_chl[r] = j;
       }
       kc += __popcll(cm);
     }
@@ -189,6 +182,17 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
   if (tid < kc) s_other[1 + n_sib + tid] = s_chl[tid];   // the children come after the siblings
   __syncthreads();
 
+  // tokens of the siblings (threads 0 .. ks-1) and of the children (threads 64 .. 64+kc-1): requested now,
+  // their probabilities under the parent's distribution gathered while the feature rows are in flight
+  const bool own_sib = tid < ks, own_ch = tid >= 64 && tid < 64 + kc;
+  int my_tok = -1;
+  if (own_sib) my_tok = a.token[lo + s_sib[tid]];
+  else if (own_ch) my_tok = a.token[lo + s_chl[tid - 64]];
+  float my_q = 0.f;
+  auto gather_q = [&]() {
+    if ((own_sib || own_ch) && my_tok >= 0 && my_tok < a.vocab) my_q = prob_of(Lp, thr, lse, my_tok);
+  };
+
   const T* row_a = H + (int64_t)gi * h;
   bool mfma_done = false;
   if constexpr (sizeof(T) == 2) {
@@ -202,6 +206,7 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
         const uint16_t* ra = l16 == 0 ? (const uint16_t*)row_a
                                       : (const uint16_t*)(H + (int64_t)(lo + s_other[min(o, n_other - 1)]) * h);
         const f32x4 acc = gram_tile(ra, ra, true, wave * kq, (wave + 1) * kq, g);
+        if (blk == 0) gather_q();
         if (blk > 0) __syncthreads();   // the previous block's partial tiles have been consumed
 #pragma unroll
         for (int r = 0; r < 4; ++r) gq[wave][(4 * g + r) * 16 + l16] = acc[r];
@@ -218,6 +223,7 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
     }
   }
   if (!mfma_done) {
+    gather_q();
     if (wave == 0) {
       float aa, dummy;
       dot2_rows(row_a, row_a, h, lane, dummy, aa);
@@ -230,6 +236,8 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
       if (lane == 0) s_cos[oi] = cos_from(ax, s_aa, xx);
     }
   }
+  if (own_sib) { s_stok[tid] = my_tok; s_sq[tid] = my_q; }
+  else if (own_ch) { s_ctok[tid - 64] = my_tok; s_cq[tid - 64] = my_q; }
   __syncthreads();
 
   if (wave == 0) {

@@ -48,6 +48,21 @@ def test_commit_matches_checker(config, layers):
     assert (glen - inp.prefix_len == 1 + ci.accept_len[ci.row_prompt]).all()
 
 
+def test_commit_grouped_heads_head_dim_64():
+    """Two prompts with guidance (four rows), 2 kv heads of 64: strides and row -> prompt mapping."""
+    from paper_2605_07230_amd import binding
+    rng = np.random.default_rng(12)
+    inp = wl.make_inputs(seed=12, name="edge", dtype="bf16", n_prompts=2, cfg=True, n_heads=4, n_kv_heads=2, head_dim=64,
+                         hidden=256, vocab=512, prefix_lens=[70, 70, 5, 5], trees=[wl.grow_tree(rng, 23, 4, 4), wl.grow_tree(rng, 9, 3, 3)],
+                         cfg_scale=3.0, temperature=1.0, top_k=50, tau_pos=0.9, tau_seq=0.9, eps_tvd=0.5, token_law="zipf")
+    ci = wl.make_commit_inputs(inp, 3, seed=12)
+    (gk, gv, glen, status), (ek, ev, elen, ovf) = _run(inp, ci)
+    assert status == binding.OK and not ovf.any()
+    np.testing.assert_array_equal(glen, elen)
+    np.testing.assert_array_equal(gk, ek)
+    np.testing.assert_array_equal(gv, ev)
+
+
 def test_commit_deepest_chain_and_zero_length():
     """Every prompt once with its forced deepest chain, once with nothing accepted."""
     from paper_2605_07230_amd import binding

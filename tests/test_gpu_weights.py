@@ -66,3 +66,21 @@ def test_weights_lumina_shaped_full_size_properties():
     t = torch.from_numpy(F).double()
     ref = torch.nn.functional.cosine_similarity(t[:, :-1], t[:, 1:], dim=-1).numpy()
     assert np.abs(cs[:, :-1] - ref).max() <= 1e-4
+
+
+def test_weights_empty_inputs_are_accepted():
+    from paper_2605_07230_amd import binding
+    dev = torch.device("cuda:0")
+    ctx = binding.Context(max_rows=1, max_nodes_total=1, max_nodes_per_tree=1, max_prefix=0, n_heads=1, head_dim=64, hidden=64, vocab=64)
+    feats = torch.zeros((0, 5, 64), dtype=torch.float32, device=dev)
+    w = torch.zeros((0, 5), dtype=torch.float32, device=dev)
+    # no sequences: nothing is launched; pointers of empty tensors may be null, so pass a dummy buffer
+    dummy = torch.zeros(16, dtype=torch.float32, device=dev)
+    a = binding.conv_weight_args()
+    a.dtype, a.n_seqs, a.seq_len, a.hidden = binding.F32, 0, 5, 64
+    a.features, a.tau_seq, a.c, a.weights, a.cos_next = dummy.data_ptr(), 0.9, 2.0, dummy.data_ptr(), None
+    import ctypes as C
+    assert ctx.lib.convergence_weights(ctx.handle, C.byref(a)) == binding.OK
+    a.n_seqs, a.hidden = 1, 65          # 260-byte rows: not a multiple of 16 bytes
+    assert ctx.lib.convergence_weights(ctx.handle, C.byref(a)) == binding.ESHAPE
+    assert ctx.device_status() == binding.OK
