@@ -229,9 +229,9 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
     ms_per_step_events = (time.perf_counter() - t1) * 1e3 / n_timed
-    names = ["attn", "attn_merge", "lmhead", "row_stats", "accept", "select"]
+    names = {0: "attn", 1: "attn_merge", 2: "lmhead", 3: "row_stats", 4: "accept", 5: "select", 8: "pack_h"}
     kernel_us = {}
-    for kid, name in enumerate(names):
+    for kid, name in names.items():
         ms, n = ds.ctx.read_kernel_timing(kid)
         if n:
             kernel_us[name] = ms * 1e3 / n

@@ -93,9 +93,9 @@ int cascade_device_status(cascade_ctx* ctx);
 /* Bytes of device workspace the ctx holds (HOST query). */
 int64_t cascade_workspace_bytes(const cascade_ctx* ctx);
 
-/* Optional per-kernel timing, for benchmarks.  When enabled, every launch of the kernels below is
- * bracketed by two HIP events recorded on the ctx stream (at most 2048 launches per kernel are
- * kept between reads; later ones are not timed).  cascade_read_kernel_timing synchronises the
+/* Optional per-kernel timing, for benchmarks.  When enabled, every launch of the kernels below
+ * carries a start and a stop HIP event that receive the dispatch's own begin / end timestamps (at
+ * most 2048 launches per kernel are kept between reads; later ones are not timed).  cascade_read_kernel_timing synchronises the
  * stream, returns the summed elapsed milliseconds and the number of timed launches of one kernel,
  * and resets that kernel's counter.  Timing is off by default and costs nothing when off. */
 typedef enum {
@@ -107,7 +107,8 @@ typedef enum {
   CASCADE_K_SELECT = 5,
   CASCADE_K_COMMIT = 6,      /* kv_commit */
   CASCADE_K_WEIGHTS = 7,     /* convergence_weights */
-  CASCADE_K_COUNT = 8
+  CASCADE_K_PACK = 8,        /* hidden-state repacking in front of the packed projection */
+  CASCADE_K_COUNT = 9
 } cascade_kernel_id;
 int cascade_set_kernel_timing(cascade_ctx* ctx, int enable);
 int cascade_read_kernel_timing(cascade_ctx* ctx, int kernel_id, double* total_ms, int32_t* launches);

@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
 hipError_t launch_accept(cascade_ctx* ctx, const accept_args* a) {
   KernelTimer t(ctx, CASCADE_K_ACCEPT);
   dim3 grid(ctx->lim.max_nodes_per_tree, a->n_prompts);
-  if (a->h_dtype == CASCADE_BF16) hipLaunchKernelGGL(accept_node_kernel<uint16_t>, grid, dim3(256), 0, ctx->stream, *a, ctx->dev_status);
-  else hipLaunchKernelGGL(accept_node_kernel<float>, grid, dim3(256), 0, ctx->stream, *a, ctx->dev_status);
+  if (a->h_dtype == CASCADE_BF16) CASCADE_TIMED_LAUNCH(t, accept_node_kernel<uint16_t>, grid, dim3(256), 0, ctx->stream, *a, ctx->dev_status);
+  else CASCADE_TIMED_LAUNCH(t, accept_node_kernel<float>, grid, dim3(256), 0, ctx->stream, *a, ctx->dev_status);
   return hipGetLastError();
 }

@@ -1027,13 +1027,13 @@ hipError_t launch_bf16_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
   if (p.n_split > 1) {
     {
       KernelTimer t(ctx, CASCADE_K_ATTN);
-      hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, true>), grid, dim3(64 * NW), smem, st, p);
+      CASCADE_TIMED_LAUNCH(t, (attn_bf16_kernel<D, NQ, NW, true>), grid, dim3(64 * NW), smem, st, p);
     }
     KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
-    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
+    CASCADE_TIMED_LAUNCH(t, (attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
   } else {
     KernelTimer t(ctx, CASCADE_K_ATTN);
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NQ, NW, false>), grid, dim3(64 * NW), smem, st, p);
+    CASCADE_TIMED_LAUNCH(t, (attn_bf16_kernel<D, NQ, NW, false>), grid, dim3(64 * NW), smem, st, p);
   }
   return hipGetLastError();
 }
@@ -1044,7 +1044,7 @@ hipError_t launch_tree_attn_f32(cascade_ctx* ctx, const tree_attn_args* a) {
   AttnParams p = make_params(ctx, a);
   dim3 grid(a->n_nodes_total, a->n_heads);
   KernelTimer t(ctx, CASCADE_K_ATTN);
-  hipLaunchKernelGGL((attn_f32_kernel<256>), grid, dim3(256), 0, ctx->stream, p, a->n_rows, a->head_dim);
+  CASCADE_TIMED_LAUNCH(t, (attn_f32_kernel<256>), grid, dim3(256), 0, ctx->stream, p, a->n_rows, a->head_dim);
   return hipGetLastError();
 }
 
@@ -1065,13 +1065,13 @@ hipError_t launch_ksplit_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
   if (p.n_split > 1) {
     {
       KernelTimer t(ctx, CASCADE_K_ATTN);
-      hipLaunchKernelGGL((attn_bf16_ksplit_kernel<D, NKG, true>), grid, dim3(NKG * 256), smem, st, p);
+      CASCADE_TIMED_LAUNCH(t, (attn_bf16_ksplit_kernel<D, NKG, true>), grid, dim3(NKG * 256), smem, st, p);
     }
     KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
-    hipLaunchKernelGGL((attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
+    CASCADE_TIMED_LAUNCH(t, (attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
   } else {
     KernelTimer t(ctx, CASCADE_K_ATTN);
-    hipLaunchKernelGGL((attn_bf16_ksplit_kernel<D, NKG, false>), grid, dim3(NKG * 256), smem, st, p);
+    CASCADE_TIMED_LAUNCH(t, (attn_bf16_ksplit_kernel<D, NKG, false>), grid, dim3(NKG * 256), smem, st, p);
   }
   return hipGetLastError();
 }
@@ -1088,7 +1088,7 @@ hipError_t launch_qsplit_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
     attr_done = true;
   }
   KernelTimer t(ctx, CASCADE_K_ATTN);
-  hipLaunchKernelGGL((attn_bf16_qsplit_kernel<D>), grid, dim3(512), smem, ctx->stream, p);
+  CASCADE_TIMED_LAUNCH(t, (attn_bf16_qsplit_kernel<D>), grid, dim3(512), smem, ctx->stream, p);
   return hipGetLastError();
 }
 

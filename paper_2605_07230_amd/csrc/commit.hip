@@ -76,6 +76,6 @@ hipError_t launch_kv_commit(cascade_ctx* ctx, const kv_commit_args* a) {
   p.tree_layer_vec = (long long)a->n_nodes_total * p.row_vec;
   dim3 grid((unsigned)(a->n_rows * (a->max_depth + 1)), (unsigned)a->n_layers);
   KernelTimer t(ctx, CASCADE_K_COMMIT);
-  kv_commit_kernel<<<grid, 256, 0, ctx->stream>>>(p);
+  CASCADE_TIMED_LAUNCH(t, kv_commit_kernel, grid, dim3(256), 0, ctx->stream, p);
   return hipGetLastError();
 }

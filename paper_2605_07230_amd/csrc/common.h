@@ -2,6 +2,7 @@
 // include/cascade_verify.h).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/cascade_verify.h"
@@ -27,20 +28,25 @@ struct cascade_ctx {
 
 enum { TIMING_RING = 2048 };
 
-// Brackets one kernel launch with two events when timing is on; otherwise does nothing.
+// Per-kernel timing: when it is on, a launch goes through hipExtLaunchKernelGGL with a start and a stop
+// event taken from the context's ring, which receive the dispatch's own begin / end timestamps (no
+// extra packets on the stream, so the figure is the kernel's duration as a profiler reports it).
 struct KernelTimer {
-  cascade_ctx* c;
-  int id, slot;
-  KernelTimer(cascade_ctx* ctx, int kernel_id) : c(ctx), id(kernel_id), slot(-1) {
+  hipEvent_t e0, e1;
+  KernelTimer(cascade_ctx* c, int id) : e0(nullptr), e1(nullptr) {
     if (c && c->timing && c->ev && c->ev_used[id] < TIMING_RING) {
-      slot = c->ev_used[id]++;
-      (void)hipEventRecord(c->ev[(id * TIMING_RING + slot) * 2], c->stream);
+      const int slot = c->ev_used[id]++;
+      e0 = c->ev[(id * TIMING_RING + slot) * 2];
+      e1 = c->ev[(id * TIMING_RING + slot) * 2 + 1];
     }
   }
-  ~KernelTimer() {
-    if (slot >= 0) (void)hipEventRecord(c->ev[(id * TIMING_RING + slot) * 2 + 1], c->stream);
-  }
+  bool active() const { return e0 != nullptr; }
 };
+#define CASCADE_TIMED_LAUNCH(timer, kernel, grid, block, smem, stream, ...)                                  \
+  do {                                                                                                       \
+    if ((timer).active()) hipExtLaunchKernelGGL(kernel, grid, block, smem, stream, (timer).e0, (timer).e1, 0, __VA_ARGS__); \
+    else hipLaunchKernelGGL(kernel, grid, block, smem, stream, __VA_ARGS__);                                  \
+  } while (0)
 
 // flags OR-ed into *dev_status by kernels
 enum {

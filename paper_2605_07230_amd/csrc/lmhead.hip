@@ -580,7 +580,7 @@ hipError_t launch_lmhead_f32(cascade_ctx* ctx, const lmhead_args* a) {
   LmParams p = make_params(a);
   dim3 grid((a->vocab + 255) / 256, a->n_nodes);
   const size_t smem = (size_t)a->hidden * sizeof(float) * (a->h_uncond ? 2 : 1);
-  hipLaunchKernelGGL(lmhead_f32_kernel, grid, dim3(256), smem, stream, p);
+  CASCADE_TIMED_LAUNCH(t, lmhead_f32_kernel, grid, dim3(256), smem, stream, p);
   return hipGetLastError();
 }
 
@@ -595,7 +595,7 @@ hipError_t launch_bf16_gemm(cascade_ctx* ctx, const LmParams& p, int grid) {
     attr_done = true;
   }
   KernelTimer t(ctx, CASCADE_K_LMHEAD);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, ctx->stream, p);
+  CASCADE_TIMED_LAUNCH(t, kern, dim3(grid), dim3(256), smem, ctx->stream, p);
   return hipGetLastError();
 }
 
@@ -616,8 +616,11 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
     uint4* hc = (uint4*)ctx->hpack_ws;
     uint4* hu = (uint4*)(ctx->hpack_ws + per);
     dim3 pgrid((a->hidden / 16 + 3) / 4, rblocks, cfg ? 2 : 1);
-    hipLaunchKernelGGL(pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_cond, hc,
-                       (const uint16_t*)a->h_uncond, hu, a->n_nodes, a->hidden);
+    {
+      KernelTimer t(ctx, CASCADE_K_PACK);
+      CASCADE_TIMED_LAUNCH(t, pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_cond, hc,
+                           (const uint16_t*)a->h_uncond, hu, a->n_nodes, a->hidden);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     p.hp_cond = hc;
@@ -632,7 +635,7 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
         attr_done[cfg] = true;
       }
       KernelTimer t(ctx, CASCADE_K_LMHEAD);
-      hipLaunchKernelGGL(kern, dim3((a->vocab / 256) * n_mtiles), dim3(256), smem, ctx->stream, p, n_mtiles);
+      CASCADE_TIMED_LAUNCH(t, kern, dim3((a->vocab / 256) * n_mtiles), dim3(256), smem, ctx->stream, p, n_mtiles);
       return hipGetLastError();
     }
     if (a->hidden == 4096) return cfg ? launch_bf16_gemm<true, 2>(ctx, p, grid) : launch_bf16_gemm<false, 2>(ctx, p, grid);
@@ -653,8 +656,8 @@ hipError_t launch_row_stats(cascade_ctx* ctx, const lmhead_args* a) {
   KernelTimer t(ctx, CASCADE_K_ROW_STATS);
   LmParams p = make_params(a);
   const int V = a->vocab;
-  if (V <= 4096) hipLaunchKernelGGL(row_stats_kernel<4>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
-  else if (V <= 16384) hipLaunchKernelGGL(row_stats_kernel<16>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
-  else hipLaunchKernelGGL(row_stats_kernel<64>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
+  if (V <= 4096) CASCADE_TIMED_LAUNCH(t, row_stats_kernel<4>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
+  else if (V <= 16384) CASCADE_TIMED_LAUNCH(t, row_stats_kernel<16>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
+  else CASCADE_TIMED_LAUNCH(t, row_stats_kernel<64>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
   return hipGetLastError();
 }

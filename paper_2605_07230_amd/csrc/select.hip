@@ -343,9 +343,9 @@ hipError_t launch_select(cascade_ctx* ctx, const select_args* a) {
   KernelTimer t(ctx, CASCADE_K_SELECT);
   const bool small_tree = ctx->lim.max_nodes_per_tree <= 256, small_vocab = a->vocab <= 16384;
   dim3 grid(a->n_prompts);
-  if (small_tree && small_vocab) hipLaunchKernelGGL((select_kernel<512, 4, 8>), grid, dim3(512), 0, ctx->stream, *a, ctx->dev_status);
-  else if (small_tree) hipLaunchKernelGGL((select_kernel<1024, 4, 16>), grid, dim3(1024), 0, ctx->stream, *a, ctx->dev_status);
-  else if (small_vocab) hipLaunchKernelGGL((select_kernel<512, 16, 8>), grid, dim3(512), 0, ctx->stream, *a, ctx->dev_status);
-  else hipLaunchKernelGGL((select_kernel<1024, 16, 16>), grid, dim3(1024), 0, ctx->stream, *a, ctx->dev_status);
+  if (small_tree && small_vocab) CASCADE_TIMED_LAUNCH(t, (select_kernel<512, 4, 8>), grid, dim3(512), 0, ctx->stream, *a, ctx->dev_status);
+  else if (small_tree) CASCADE_TIMED_LAUNCH(t, (select_kernel<1024, 4, 16>), grid, dim3(1024), 0, ctx->stream, *a, ctx->dev_status);
+  else if (small_vocab) CASCADE_TIMED_LAUNCH(t, (select_kernel<512, 16, 8>), grid, dim3(512), 0, ctx->stream, *a, ctx->dev_status);
+  else CASCADE_TIMED_LAUNCH(t, (select_kernel<1024, 16, 16>), grid, dim3(1024), 0, ctx->stream, *a, ctx->dev_status);
   return hipGetLastError();
 }

@@ -234,7 +234,7 @@ hipError_t launch_select_residual(cascade_ctx* ctx, const select_args* a) {
   dim3 grid(a->n_prompts);
   const int V = a->vocab;
 #define CASCADE_LAUNCH_RESIDUAL(VQ, EX) \
-  hipLaunchKernelGGL((select_residual_kernel<VQ, EX>), grid, dim3(1024), 0, ctx->stream, *a, ctx->dev_status)
+  CASCADE_TIMED_LAUNCH(t, (select_residual_kernel<VQ, EX>), grid, dim3(1024), 0, ctx->stream, *a, ctx->dev_status)
   if (V <= 16 * 256) { if (V == 16 * 256) CASCADE_LAUNCH_RESIDUAL(1, true); else CASCADE_LAUNCH_RESIDUAL(1, false); }
   else if (V <= 16 * 1024) { if (V == 16 * 1024) CASCADE_LAUNCH_RESIDUAL(4, true); else CASCADE_LAUNCH_RESIDUAL(4, false); }
   else { if (V == 16 * 4096) CASCADE_LAUNCH_RESIDUAL(16, true); else CASCADE_LAUNCH_RESIDUAL(16, false); }

@@ -105,7 +105,8 @@ hipError_t launch_t(cascade_ctx* ctx, const conv_weight_args* a) {
   const int runs_per_seq = a->seq_len > 1 ? (a->seq_len - 1 + RUN - 1) / RUN : 1;
   const long long waves = (long long)a->n_seqs * runs_per_seq;
   dim3 grid((unsigned)((waves + 3) / 4));
-#define CASCADE_LAUNCH_CW(NV) hipLaunchKernelGGL((conv_weight_kernel<T, NV>), grid, dim3(256), 0, ctx->stream, *a, runs_per_seq, RUN)
+  KernelTimer t(ctx, CASCADE_K_WEIGHTS);
+#define CASCADE_LAUNCH_CW(NV) CASCADE_TIMED_LAUNCH(t, (conv_weight_kernel<T, NV>), grid, dim3(256), 0, ctx->stream, *a, runs_per_seq, RUN)
   if (nv <= 1) CASCADE_LAUNCH_CW(1);
   else if (nv <= 2) CASCADE_LAUNCH_CW(2);
   else if (nv <= 4) CASCADE_LAUNCH_CW(4);
@@ -118,6 +119,5 @@ hipError_t launch_t(cascade_ctx* ctx, const conv_weight_args* a) {
 }  // namespace
 
 hipError_t launch_conv_weights(cascade_ctx* ctx, const conv_weight_args* a) {
-  KernelTimer t(ctx, CASCADE_K_WEIGHTS);
   return a->dtype == CASCADE_BF16 ? launch_t<uint16_t>(ctx, a) : launch_t<float>(ctx, a);
 }
