@@ -533,7 +533,7 @@ __global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams 
     const bool tree_tile = t >= n_pt;
     const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
     const int klimit = tree_tile ? T : P;
-    __syncthreads();   // previous round's tiles are consumed (and, in round 0, the parent array is complete)
+    __syncthreads();   // the previous pass's tiles are consumed (and, before the first pass, the parent array is complete)
 #pragma unroll
     for (int it = 0; it < NPC; ++it) {
       const int c = gl + 256 * it, key = c / DC, dc = c % DC;
