@@ -314,14 +314,16 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
 // LDS-tiled projection for steps with several hundred rows (batched prompts), where the kernel is
 // bound by the matrix cores instead of by streaming W.  Workgroup tile = 256 rows x 256 vocabulary
 // columns: with guidance 128 nodes (4 conditional + 4 unconditional 32-row blocks), without 256
-// nodes.  The four waves form a 2 x 2 grid; a wave owns 4 row blocks (two node blocks, conditional
-// and unconditional, so the mix stays in registers) x 4 column blocks = 16 accumulators.  Both
+// nodes.  The eight waves form a 2 x 4 grid; a wave owns 4 row blocks (two node blocks, conditional
+// and unconditional, so the mix stays in registers) x 2 column blocks = 8 accumulators and at most
+// 256 registers, so two waves share a SIMD and one wave's waits are covered by the other's MFMAs
+// (a 2 x 2 grid of four waves with 16 accumulators each was 2-4 % slower).  Both
 // operands arrive packed in MFMA operand order, so global -> register -> LDS -> register moves are
 // all contiguous 16-byte pieces in lane order (no bank conflicts, no shuffles).  Stages of four
 // k16 steps (64 KiB) are double-buffered in LDS; the next stage's global loads are issued before
 // the current stage's MFMAs.
 template <bool CFG>
-__global__ __launch_bounds__(256) void lmhead_bf16_tiled_kernel(LmParams p, int n_mtiles) {
+__global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int n_mtiles) {
   extern __shared__ u32x4 lds[];     // [2 stages][4 k16 steps][16 blocks: 8 A then 8 B][64 lanes]
   constexpr int BK = 4, STAGE = BK * 16 * 64;   // uint4 per stage
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -333,12 +335,12 @@ __global__ __launch_bounds__(256) void lmhead_bf16_tiled_kernel(LmParams p, int 
   if ((nwg & 7) == 0) logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
   const int nt = logical / n_mtiles, mt = logical % n_mtiles;
 
-  // loader: piece q = tid + 256 i -> k16 step i / 4, block wave + 4 (i % 4), lane: a wave always copies
-  // whole 1 KiB blocks, and a thread needs only four base pointers (one per block it serves)
-  const u32x4* src[4];
+  // loader: piece q = tid + 512 i -> k16 step i / 2, block wave + 8 (i % 2), lane: a wave always copies
+  // whole 1 KiB blocks, and a thread needs only two base pointers (one per block it serves)
+  const u32x4* src[2];
 #pragma unroll
-  for (int b4 = 0; b4 < 4; ++b4) {
-    const int blk = wave + 4 * b4;
+  for (int b4 = 0; b4 < 2; ++b4) {
+    const int blk = wave + 8 * b4;
     const u32x4* base;
     int64_t rb;   // 32-row block index in the source matrix
     if (blk < 8) {
@@ -353,36 +355,36 @@ __global__ __launch_bounds__(256) void lmhead_bf16_tiled_kernel(LmParams p, int 
   // two register sets: while stage st is multiplied out of LDS, stage st+1 sits in one set (arrived,
   // about to be written to the other LDS buffer) and stage st+2 is in flight into the other set —
   // 128 KiB of requests per CU, which is what it takes to cover the L2 / HBM latency at this rate
-  u32x4 stg[2][16];
+  u32x4 stg[2][8];
   auto request_stage = [&](int set, int st) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) stg[set][i] = src[i & 3][((int64_t)st * BK + (i >> 2)) * 64];
+    for (int i = 0; i < 8; ++i) stg[set][i] = src[i & 1][((int64_t)st * BK + (i >> 1)) * 64];
   };
   auto store_stage = [&](int set, int buf) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) lds[buf * STAGE + tid + 256 * i] = stg[set][i];
+    for (int i = 0; i < 8; ++i) lds[buf * STAGE + tid + 512 * i] = stg[set][i];
   };
 
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;
   int ablk[4];
   if (CFG) { ablk[0] = 2 * wm; ablk[1] = 2 * wm + 1; ablk[2] = 4 + 2 * wm; ablk[3] = 5 + 2 * wm; }
   else { ablk[0] = 4 * wm; ablk[1] = 4 * wm + 1; ablk[2] = 4 * wm + 2; ablk[3] = 4 * wm + 3; }
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // operand fragments are double-buffered in registers: step ks+1 is read from LDS while step ks multiplies
-  Frag8 fa[2][4], fb[2][4];
+  Frag8 fa[2][4], fb[2][2];
   auto read_frags = [&](int slot, int buf, int ks) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) fa[slot][i].n = lds[buf * STAGE + (ks * 16 + ablk[i]) * 64 + lane];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fb[slot][j].n = lds[buf * STAGE + (ks * 16 + 8 + 4 * wn + j) * 64 + lane];
+    for (int j = 0; j < 2; ++j) fb[slot][j].n = lds[buf * STAGE + (ks * 16 + 8 + 2 * wn + j) * 64 + lane];
   };
   auto compute_stage = [&](int buf, int set_to_store) {
 #pragma unroll
@@ -392,7 +394,7 @@ __global__ __launch_bounds__(256) void lmhead_bf16_tiled_kernel(LmParams p, int 
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i].v, fb[ks & 1][j].v, acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       // the other LDS buffer was released by the barrier that ended the previous iteration; fill it
@@ -417,12 +419,12 @@ __global__ __launch_bounds__(256) void lmhead_bf16_tiled_kernel(LmParams p, int 
   }
 
   // epilogue: accumulator (i, j), register r of lane (r32, half) is row 8 (r / 4) + 4 half + r % 4, column r32
-  const int v0 = nt * 256 + 128 * wn;
+  const int v0 = nt * 256 + 64 * wn;
 #pragma unroll
   for (int i = 0; i < (CFG ? 2 : 4); ++i) {
     const int node0 = CFG ? mt * 128 + 32 * (2 * wm + i) : mt * 256 + 32 * (4 * wm + i);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const float c = acc[i][j][r];
@@ -635,7 +637,7 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
         attr_done[cfg] = true;
       }
       KernelTimer t(ctx, CASCADE_K_LMHEAD);
-      CASCADE_TIMED_LAUNCH(t, kern, dim3((a->vocab / 256) * n_mtiles), dim3(256), smem, ctx->stream, p, n_mtiles);
+      CASCADE_TIMED_LAUNCH(t, kern, dim3((a->vocab / 256) * n_mtiles), dim3(512), smem, ctx->stream, p, n_mtiles);
       return hipGetLastError();
     }
     if (a->hidden == 4096) return cfg ? launch_bf16_gemm<true, 2>(ctx, p, grid) : launch_bf16_gemm<false, 2>(ctx, p, grid);
