@@ -81,6 +81,9 @@ class DecodeLoop:
         self.prefix_len_next = torch.empty_like(self.prefix_len)
         self.row_prompt = torch.zeros(S, dtype=torch.int32, device=self.dev)
         self.prefix_host = int(first.prefix_len.max())
+        self.h_len = torch.empty(1, dtype=torch.int32, pin_memory=True)
+        self.h_tvd = torch.empty(1, dtype=torch.float32, pin_memory=True)
+        self.h_emit = torch.empty((1, self.max_depth + 1), dtype=torch.int32, pin_memory=True)
 
     def run(self, mode: int = binding.WALK_SEQUENTIAL, record: bool = False, max_steps: Optional[int] = None) -> LoopResult:
         accept_lens, tvds, emitted, records = [], [], [], [] if record else None
@@ -101,11 +104,16 @@ class DecodeLoop:
                               k_cache=self.k_cache, v_cache=self.v_cache, prefix_len=self.prefix_len,
                               prefix_len_out=self.prefix_len_next)
             self.prefix_len, self.prefix_len_next = self.prefix_len_next, self.prefix_len
-            # the host needs the accepted length to know how far the image has advanced (one small read-back)
-            a_len = int(st.accept_len.cpu()[0])
+            # the host needs the accepted length to know how far the image has advanced: three small
+            # asynchronous copies into pinned memory and one wait for the stream
+            self.h_len.copy_(st.accept_len, non_blocking=True)
+            self.h_tvd.copy_(st.tvd_used, non_blocking=True)
+            self.h_emit[:, :st.emitted.shape[1]].copy_(st.emitted, non_blocking=True)
+            torch.cuda.current_stream().synchronize()
+            a_len = int(self.h_len[0])
             accept_lens.append(a_len)
-            tvds.append(float(st.tvd_used.cpu()[0]))
-            emitted.append(st.emitted.cpu()[0, :a_len + 1].tolist())
+            tvds.append(float(self.h_tvd[0]))
+            emitted.append(self.h_emit[0, :a_len + 1].tolist())
             if record:
                 records.append(dict(pool_index=n % len(self.steps), attn_out=st.attn_out.float().cpu().numpy(),
                                     logits=st.logits.cpu().numpy(), row_thr=st.row_thr.cpu().numpy(),
