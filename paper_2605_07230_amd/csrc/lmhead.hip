@@ -222,7 +222,12 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
     // fragment of a later step never waits for younger W requests.
     constexpr int HD = 8, WD = 16;
     static_assert(!DEEP || (NSTEPS % 8 == 0 && NSTEPS >= WD), "whole 128-wide slices per wave");
-    auto ks_of_step = [&](int t) { return (wave + 4 * (t >> 3)) * 8 + (t & 7); };
+    // Workgroups that run side by side start at different slices of the hidden dimension (rot), so
+    // that at any moment they read different parts of H (spread over the L2 channels instead of all
+    // hitting the same lines) and their W streams differ in the low address bits as well.
+    constexpr int NSL = NSTEPS / 8;                               // slices per wave (a power of two is not required)
+    const int rot = __builtin_amdgcn_readfirstlane(((blockIdx.x >> 3) + (blockIdx.x & 7)) % NSL);
+    auto ks_of_step = [&](int t) { return (wave + 4 * (((t >> 3) + rot) % NSL)) * 8 + (t & 7); };
     Frag8 hr[HD][NA];
     Frag8 wr[WD][2];
     auto load_h = [&](int slot, int t) {
@@ -326,9 +331,11 @@ template <bool CFG>
 __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int n_mtiles) {
   extern __shared__ u32x4 lds[];     // [2 stages][4 k16 steps][16 blocks: 8 A then 8 B][64 lanes]
   constexpr int BK = 4, STAGE = BK * 16 * 64;   // uint4 per stage
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: everything derived from it stays scalar
   const int r32 = lane & 31, half = lane >> 5;
   const int KS = p.hidden / 16, n_stages = KS / BK;
+  const unsigned lane_off = 16u * lane;                        // byte offset of this lane's 16-byte piece in a block
 
   int logical = blockIdx.x;
   const int nwg = gridDim.x;
@@ -336,21 +343,21 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
   const int nt = logical / n_mtiles, mt = logical % n_mtiles;
 
   // loader: piece q = tid + 512 i -> k16 step i / 2, block wave + 8 (i % 2), lane: a wave always copies
-  // whole 1 KiB blocks, and a thread needs only two base pointers (one per block it serves)
-  const u32x4* src[2];
+  // whole 1 KiB blocks; its two block pointers are scalars, the lane adds its 16-byte offset
+  const char* src[2];
 #pragma unroll
   for (int b4 = 0; b4 < 2; ++b4) {
     const int blk = wave + 8 * b4;
-    const u32x4* base;
+    const char* base;
     int64_t rb;   // 32-row block index in the source matrix
     if (blk < 8) {
-      if (CFG) { base = (const u32x4*)(blk < 4 ? p.hp_cond : p.hp_uncond); rb = (int64_t)mt * 4 + (blk & 3); }
-      else { base = (const u32x4*)p.hp_cond; rb = (int64_t)mt * 8 + blk; }
+      if (CFG) { base = (const char*)(blk < 4 ? p.hp_cond : p.hp_uncond); rb = (int64_t)mt * 4 + (blk & 3); }
+      else { base = (const char*)p.hp_cond; rb = (int64_t)mt * 8 + blk; }
     } else {
-      base = (const u32x4*)p.w;
+      base = (const char*)p.w;
       rb = (int64_t)nt * 8 + (blk - 8);
     }
-    src[b4] = base + rb * KS * 64 + lane;
+    src[b4] = base + rb * KS * 1024;
   }
   // two register sets: while stage st is multiplied out of LDS, stage st+1 sits in one set (arrived,
   // about to be written to the other LDS buffer) and stage st+2 is in flight into the other set —
@@ -358,17 +365,27 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
   u32x4 stg[2][8];
   auto request_stage = [&](int set, int st) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) stg[set][i] = src[i & 1][((int64_t)st * BK + (i >> 1)) * 64];
+    for (int i = 0; i < 8; ++i)
+      stg[set][i] = *(const u32x4*)(src[i & 1] + ((int64_t)st * BK + (i >> 1)) * 1024 + lane_off);
   };
+  // LDS addresses: one base register per (role, buffer) and compile-time offsets below 64 KiB, which
+  // fit the instructions' immediate field.  The bases are made opaque so that the compiler neither
+  // re-derives them nor keeps further sums alive: the loop runs at the register limit, and a spilled
+  // address would be reloaded behind a wait for ALL outstanding global loads.
+  char* const lds_b = (char*)lds;
+  auto opaque = [](unsigned x) { asm volatile("" : "+v"(x)); return x; };
+  const unsigned st_off[2] = {opaque(1024u * wave + lane_off), opaque(1024u * wave + lane_off + STAGE * 16)};
   auto store_stage = [&](int set, int buf) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) lds[buf * STAGE + tid + 512 * i] = stg[set][i];
+    for (int i = 0; i < 8; ++i) *(u32x4*)(lds_b + st_off[buf] + 8192 * i) = stg[set][i];
   };
 
+  // row blocks of wave row wm: with guidance 2 wm, 2 wm + 1 (conditional) and the same two of the
+  // unconditional half (+4); without, 4 wm .. 4 wm + 3: one base address plus constant offsets
   const int wm = wave >> 2, wn = wave & 3;
-  int ablk[4];
-  if (CFG) { ablk[0] = 2 * wm; ablk[1] = 2 * wm + 1; ablk[2] = 4 + 2 * wm; ablk[3] = 5 + 2 * wm; }
-  else { ablk[0] = 4 * wm; ablk[1] = 4 * wm + 1; ablk[2] = 4 * wm + 2; ablk[3] = 4 * wm + 3; }
+  const unsigned a_base = 1024u * (CFG ? 2 * wm : 4 * wm) + lane_off, b_base = 1024u * (8 + 2 * wn) + lane_off;
+  const unsigned a_off[2] = {opaque(a_base), opaque(a_base + STAGE * 16)};
+  const unsigned b_off[2] = {opaque(b_base), opaque(b_base + STAGE * 16)};
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -382,9 +399,13 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
   Frag8 fa[2][4], fb[2][2];
   auto read_frags = [&](int slot, int buf, int ks) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[slot][i].n = lds[buf * STAGE + (ks * 16 + ablk[i]) * 64 + lane];
+    for (int i = 0; i < 4; ++i) {
+      const int rel = CFG ? (i & 1) + 4 * (i >> 1) : i;
+      fa[slot][i].n = *(const u32x4*)(lds_b + a_off[buf] + (ks * 16 + rel) * 1024);
+    }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) fb[slot][j].n = lds[buf * STAGE + (ks * 16 + 8 + 2 * wn + j) * 64 + lane];
+    for (int j = 0; j < 2; ++j)
+      fb[slot][j].n = *(const u32x4*)(lds_b + b_off[buf] + (ks * 16 + j) * 1024);
   };
   auto compute_stage = [&](int buf, int set_to_store) {
 #pragma unroll
