@@ -320,21 +320,31 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
 // bound by the matrix cores instead of by streaming W.  Workgroup tile = 256 rows x 256 vocabulary
 // columns: with guidance 128 nodes (4 conditional + 4 unconditional 32-row blocks), without 256
 // nodes.  The eight waves form a 2 x 4 grid; a wave owns 4 row blocks (two node blocks, conditional
-// and unconditional, so the mix stays in registers) x 2 column blocks = 8 accumulators and at most
-// 256 registers, so two waves share a SIMD and one wave's waits are covered by the other's MFMAs
-// (a 2 x 2 grid of four waves with 16 accumulators each was 2-4 % slower).  Both
-// operands arrive packed in MFMA operand order, so global -> register -> LDS -> register moves are
-// all contiguous 16-byte pieces in lane order (no bank conflicts, no shuffles).  Stages of four
-// k16 steps (64 KiB) are double-buffered in LDS; the next stage's global loads are issued before
-// the current stage's MFMAs.
+// and unconditional, so the mix stays in registers) x 2 column blocks = 8 accumulators, two waves
+// share a SIMD and one wave's waits are covered by the other's MFMAs (four waves with 16
+// accumulators each were 10 % slower).
+//
+// Both operands are packed in MFMA operand order and never pass through registers on their way in:
+// gfx950's 16-byte LDS-direct loads write each wave-wide 1 KiB block straight into a ring of four
+// half-stages (2 k16 steps = 32 KiB each), so there are no staging registers, no LDS store
+// instructions and no register pressure in the loop (a register-staged version of this kernel ran
+// at the 256-register limit; a single spilled address in its loop was reloaded behind a wait for
+// all outstanding loads and cost 8 %).  Per half-stage h:
+//   - step 0 is multiplied; between the multiplications (each occupies the matrix core for 32
+//     cycles, so the other instructions are free) step 1's fragments are read and the loads of
+//     half-stage h + 3 are issued into the buffer that h - 1 was read from;
+//   - the wave waits for its own loads of h + 1 and for its LDS reads, then the workgroup barrier
+//     (bare: a fenced barrier would wait for every outstanding load);
+//   - step 1 is multiplied while the first fragments of h + 1 are read.
+// The barrier sits before the last step's multiplications, which cover it.
 template <bool CFG>
 __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int n_mtiles) {
-  extern __shared__ u32x4 lds[];     // [2 stages][4 k16 steps][16 blocks: 8 A then 8 B][64 lanes]
-  constexpr int BK = 4, STAGE = BK * 16 * 64;   // uint4 per stage
+  extern __shared__ u32x4 lds[];     // [4 half-stages][2 k16 steps][16 blocks: 8 H then 8 W][64 lanes]
+  constexpr int NBUF = 4, HS = 2, HBYTES = HS * 16 * 1024;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: everything derived from it stays scalar
   const int r32 = lane & 31, half = lane >> 5;
-  const int KS = p.hidden / 16, n_stages = KS / BK;
+  const int KS = p.hidden / 16, n_half = KS / HS;
   const unsigned lane_off = 16u * lane;                        // byte offset of this lane's 16-byte piece in a block
 
   int logical = blockIdx.x;
@@ -342,50 +352,45 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
   if ((nwg & 7) == 0) logical = (blockIdx.x & 7) * (nwg >> 3) + (blockIdx.x >> 3);
   const int nt = logical / n_mtiles, mt = logical % n_mtiles;
 
-  // loader: piece q = tid + 512 i -> k16 step i / 2, block wave + 8 (i % 2), lane: a wave always copies
-  // whole 1 KiB blocks; its two block pointers are scalars, the lane adds its 16-byte offset
+  // loader: per k16 step a wave copies block wave (H) and block wave + 8 (W); both base pointers are scalars
   const char* src[2];
 #pragma unroll
   for (int b4 = 0; b4 < 2; ++b4) {
-    const int blk = wave + 8 * b4;
     const char* base;
     int64_t rb;   // 32-row block index in the source matrix
-    if (blk < 8) {
-      if (CFG) { base = (const char*)(blk < 4 ? p.hp_cond : p.hp_uncond); rb = (int64_t)mt * 4 + (blk & 3); }
-      else { base = (const char*)p.hp_cond; rb = (int64_t)mt * 8 + blk; }
+    if (b4 == 0) {
+      if (CFG) { base = (const char*)(wave < 4 ? p.hp_cond : p.hp_uncond); rb = (int64_t)mt * 4 + (wave & 3); }
+      else { base = (const char*)p.hp_cond; rb = (int64_t)mt * 8 + wave; }
     } else {
       base = (const char*)p.w;
-      rb = (int64_t)nt * 8 + (blk - 8);
+      rb = (int64_t)nt * 8 + wave;
     }
     src[b4] = base + rb * KS * 1024;
   }
-  // two register sets: while stage st is multiplied out of LDS, stage st+1 sits in one set (arrived,
-  // about to be written to the other LDS buffer) and stage st+2 is in flight into the other set —
-  // 128 KiB of requests per CU, which is what it takes to cover the L2 / HBM latency at this rate
-  u32x4 stg[2][8];
-  auto request_stage = [&](int set, int st) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      stg[set][i] = *(const u32x4*)(src[i & 1] + ((int64_t)st * BK + (i >> 1)) * 1024 + lane_off);
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)lds);
+  const int last = n_half - 1;
+  // request i of a half-stage: k16 step i / 2, H (i even) or W (i odd).  h may run past the end:
+  // clamped, that data is never multiplied.  M0 carries the LDS address of the wave's 1 KiB block;
+  // each lane's 16 bytes land at 16 * lane behind it.
+  auto request = [&](int h, int buf, int i) {
+    const char* g = src[i & 1] + ((int64_t)min(h, last) * HS + (i >> 1)) * 1024;
+    const unsigned l = lds0 + buf * HBYTES + ((i >> 1) * 16 + wave + 8 * (i & 1)) * 1024;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(lane_off), "s"(g) : "memory");
   };
-  // LDS addresses: one base register per (role, buffer) and compile-time offsets below 64 KiB, which
-  // fit the instructions' immediate field.  The bases are made opaque so that the compiler neither
-  // re-derives them nor keeps further sums alive: the loop runs at the register limit, and a spilled
-  // address would be reloaded behind a wait for ALL outstanding global loads.
+  // A wave's own loads of the next half-stage have landed when at most the 2 x 4 later ones are
+  // outstanding; its LDS reads are complete at lgkmcnt(0).
+  auto land_and_sync = [&]() { asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+  // LDS read addresses: one base register per 64 KiB and role, the rest is an immediate.  The bases
+  // are made opaque so that the compiler neither re-derives them nor keeps further sums alive.
   char* const lds_b = (char*)lds;
   auto opaque = [](unsigned x) { asm volatile("" : "+v"(x)); return x; };
-  const unsigned st_off[2] = {opaque(1024u * wave + lane_off), opaque(1024u * wave + lane_off + STAGE * 16)};
-  auto store_stage = [&](int set, int buf) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) *(u32x4*)(lds_b + st_off[buf] + 8192 * i) = stg[set][i];
-  };
-
-  // row blocks of wave row wm: with guidance 2 wm, 2 wm + 1 (conditional) and the same two of the
-  // unconditional half (+4); without, 4 wm .. 4 wm + 3: one base address plus constant offsets
   const int wm = wave >> 2, wn = wave & 3;
+  // row blocks of wave row wm: with guidance 2 wm, 2 wm + 1 (conditional) and the same two of the
+  // unconditional half (+4); without, 4 wm .. 4 wm + 3
   const unsigned a_base = 1024u * (CFG ? 2 * wm : 4 * wm) + lane_off, b_base = 1024u * (8 + 2 * wn) + lane_off;
-  const unsigned a_off[2] = {opaque(a_base), opaque(a_base + STAGE * 16)};
-  const unsigned b_off[2] = {opaque(b_base), opaque(b_base + STAGE * 16)};
+  const unsigned a_off[2] = {opaque(a_base), opaque(a_base + 65536u)};
+  const unsigned b_off[2] = {opaque(b_base), opaque(b_base + 65536u)};
 
   f32x16 acc[4][2];
 #pragma unroll
@@ -395,49 +400,49 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // operand fragments are double-buffered in registers: step ks+1 is read from LDS while step ks multiplies
-  Frag8 fa[2][4], fb[2][2];
-  auto read_frags = [&](int slot, int buf, int ks) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int rel = CFG ? (i & 1) + 4 * (i >> 1) : i;
-      fa[slot][i].n = *(const u32x4*)(lds_b + a_off[buf] + (ks * 16 + rel) * 1024);
+  Frag8 fa[2][4], fb[2][2];   // operand fragments, double-buffered by k16 step
+  auto read_one = [&](int slot, int buf, int ks, int idx) {   // idx 0-3: H fragment, 4-5: W fragment
+    const int byte0 = buf * HBYTES + ks * 16 * 1024;          // compile-time after unrolling
+    if (idx < 4) {
+      const int rel = CFG ? (idx & 1) + 4 * (idx >> 1) : idx;
+      fa[slot][idx].n = *(const u32x4*)(lds_b + a_off[byte0 >> 16] + ((byte0 & 65535) + rel * 1024));
+    } else {
+      fb[slot][idx - 4].n = *(const u32x4*)(lds_b + b_off[byte0 >> 16] + ((byte0 & 65535) + (idx - 4) * 1024));
     }
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-      fb[slot][j].n = *(const u32x4*)(lds_b + b_off[buf] + (ks * 16 + j) * 1024);
   };
-  auto compute_stage = [&](int buf, int set_to_store) {
+  // eight multiplications; after the k-th one, side(k) issues its piece of the other work
+  auto multiply_with = [&](int slot, auto&& side) {
 #pragma unroll
-    for (int ks = 0; ks < BK; ++ks) {
-      if (ks + 1 < BK) read_frags((ks + 1) & 1, buf, ks + 1);
+    for (int k = 0; k < 8; ++k) {
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i].v, fb[ks & 1][j].v, acc[i][j], 0, 0, 0);
+      acc[k >> 1][k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][k >> 1].v, fb[slot][k & 1].v, acc[k >> 1][k & 1], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      // the other LDS buffer was released by the barrier that ended the previous iteration; fill it
-      // while the matrix cores work through this stage
-      if (ks == 1) store_stage(set_to_store, buf ^ 1);
+      side(k);
     }
-    __syncthreads();
-    read_frags(0, buf ^ 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
   };
-  // stage indices past the end are clamped: redundant loads and LDS writes, but no branches
-  const int last = n_stages - 1;
-  request_stage(0, 0);
-  request_stage(1, min(1, last));
-  store_stage(0, 0);
-  __syncthreads();
-  read_frags(0, 0, 0);
-  for (int st = 0; st < n_stages; st += 2) {   // n_stages is even (hidden is a multiple of 128)
-    request_stage(0, min(st + 2, last));
-    compute_stage(0, 1);                        // multiplies stage st, writes stage st+1 (set 1) to LDS buffer 1
-    request_stage(1, min(st + 3, last));
-    compute_stage(1, 0);                        // multiplies stage st+1, writes stage st+2 (set 0) to LDS buffer 0
+  constexpr int FRAG_ORDER[6] = {0, 4, 5, 1, 2, 3};   // the order in which the multiplications first need them
+
+#pragma unroll
+  for (int h = 0; h < NBUF - 1; ++h)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) request(h, h, i);
+  land_and_sync();
+#pragma unroll
+  for (int k = 0; k < 6; ++k) read_one(0, 0, 0, FRAG_ORDER[k]);
+  for (int h0 = 0; h0 < n_half; h0 += NBUF) {   // hidden is a multiple of 128: four half-stages always divide it
+#pragma unroll
+    for (int b = 0; b < NBUF; ++b) {
+      const int hn = h0 + b + NBUF - 1, bn = (b + NBUF - 1) % NBUF;
+      multiply_with(0, [&](int k) {
+        if (k < 6) read_one(1, b, 1, FRAG_ORDER[k]);
+        else { request(hn, bn, 2 * (k - 6)); request(hn, bn, 2 * (k - 6) + 1); }
+      });
+      land_and_sync();
+      multiply_with(1, [&](int k) { if (k < 6) read_one(0, (b + 1) % NBUF, 0, FRAG_ORDER[k]); });
+    }
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the clamped extra requests must not outlive the workgroup's LDS
 
   // epilogue: accumulator (i, j), register r of lane (r32, half) is row 8 (r / 4) + 4 half + r % 4, column r32
   const int v0 = nt * 256 + 64 * wn;
@@ -452,7 +457,7 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
         const float gmix = CFG ? acc[i + 2][j][r] + p.cfg_scale * (c - acc[i + 2][j][r]) : c;
         const int node = node0 + 8 * (r >> 2) + 4 * half + (r & 3);
         if (node < p.n_nodes) p.logits[(int64_t)node * p.vocab + v0 + 32 * j + r32] = gmix / p.temperature;
-        if (r == 15) __builtin_amdgcn_sched_barrier(0);   // one accumulator pair at a time leaves the AGPRs
+        if (r == 15) __builtin_amdgcn_sched_barrier(0);
       }
   }
 }
@@ -649,7 +654,7 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
     p.hp_cond = hc;
     p.hp_uncond = hu;
     if (tiled) {
-      const size_t smem = (size_t)2 * 4 * 16 * 64 * sizeof(uint4);   // 128 KiB
+      const size_t smem = (size_t)4 * 32 * 1024;   // ring of four 32 KiB half-stages
       static bool attr_done[2] = {false, false};
       auto kern = cfg ? lmhead_bf16_tiled_kernel<true> : lmhead_bf16_tiled_kernel<false>;
       if (!attr_done[cfg]) {

@@ -22,12 +22,29 @@ def _kernel_stats(src, tmp_path):
     assert r.returncode == 0, r.stderr
     text = open(out).read()
     stats = re.findall(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.vgpr_spill_count:\s+(\d+)", text)
-    return stats
+    return stats, text
 
 
 @pytest.mark.parametrize("src", HOT)
 def test_hot_kernels_do_not_spill(src, tmp_path):
-    stats = _kernel_stats(src, tmp_path)
+    stats, _ = _kernel_stats(src, tmp_path)
     assert stats, "no kernels found in the assembly"
     bad = [(name, int(n)) for name, n in stats if int(n) and not any(a in name for a in ALLOWED)]
     assert not bad, bad
+
+
+def test_tiled_projection_m0_and_waits(tmp_path):
+    """The tiled projection sets M0 by hand for its LDS-direct loads (the compiler is not told), and
+    its software pipeline relies on partial waits: M0 must have no other user in that kernel, and
+    its main loop must not contain a wait for ALL outstanding loads."""
+    _, text = _kernel_stats("lmhead.hip", tmp_path)
+    bodies = re.findall(r"^(_ZN\S*lmhead_bf16_tiled_kernel\S*):[^\n]*\n(.*?)s_endpgm", text, flags=re.S | re.M)
+    assert len(bodies) == 2
+    for name, body in bodies:
+        m0 = [l.strip() for l in body.splitlines() if re.search(r"\bm0\b", l)]
+        assert m0 and all(l.startswith("s_mov_b32 m0,") for l in m0), (name, m0[:5])
+        assert body.count("global_load_lds_dwordx4") >= 16
+        loop = body[body.index("Inner Loop Header"):]
+        loop = loop[:loop.index("s_cbranch_scc")]
+        assert "vmcnt(0)" not in loop, name
+        assert loop.count("s_barrier") == 4 and loop.count("v_mfma_f32_32x32x16_bf16") == 64
