@@ -154,6 +154,21 @@ def test_temperature_and_no_guidance(packed):
     pu.check_accept_and_path(inp, ds)
 
 
+@pytest.mark.parametrize("hidden,cfg", [(128, True), (384, True), (640, False)])
+def test_tiled_projection_short_hidden_and_ragged_row_tiles(hidden, cfg):
+    """The LDS-tiled projection (>= 512 rows) at hidden sizes of one, three and five ring rounds,
+    with a last row tile that is almost empty; every logit is compared."""
+    rng = np.random.default_rng(11)
+    sizes = [100, 97, 63] if cfg else [200, 200, 130]          # 260 nodes x 2 rows / 530 rows: three row tiles
+    trees = [wl.grow_tree(rng, n, 6, 8) for n in sizes]
+    print(f"[tiled small] hidden={hidden} cfg={cfg}", flush=True)
+    inp = _small_bf16(11, n_prompts=3, cfg=cfg, hidden=hidden, vocab=512, trees=trees,
+                      prefix_lens=[33, 33, 20, 20, 7, 7] if cfg else [33, 20, 7], top_k=40)
+    ds = pu.run_gpu_step(inp, packed_w=True)
+    pu.check_lmhead(inp, ds)
+    pu.check_accept_and_path(inp, ds, require_margin=False)
+
+
 def test_packed_and_row_major_weights_agree_bitwise_on_statistics():
     inp = _small_bf16(6, n_prompts=1, prefix_lens=[9, 9], trees=[wl.grow_tree(np.random.default_rng(6), 70, 5, 6)])
     a = pu.run_gpu_step(inp)
