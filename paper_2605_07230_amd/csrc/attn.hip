@@ -769,27 +769,24 @@ __global__ __launch_bounds__(512) void attn_bf16_qsplit_kernel(AttnParams p) {
     const uint16_t* ksrc = tree_tile ? ktr : kc;
     const uint16_t* vsrc = tree_tile ? vtr : vc;
     const int64_t pitch = tree_tile ? tree_pitch : p.sp;
-    const int last = max(klimit - 1, 0);   // clamped row for loads past the end (zeroed below)
+    // Keys past the end of the tile's source are read from its last row (clamped: always in bounds)
+    // and are NOT zeroed here: their scores are masked to -inf below, so their probabilities are
+    // exactly 0 and the clamped (finite) K and V rows contribute nothing.  A select on the loaded
+    // value would make the compiler wait for every load right here, before the next one is issued.
+    const int last = max(klimit - 1, 0);
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
       const int key = kbase + 16 * kt + l16;
       const uint16_t* kp = ksrc + (int64_t)min(key, last) * pitch + 8 * g;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const u32x4 x = *(const u32x4*)(kp + 32 * ks);
-        kf[kt][ks] = (t < nt && key < klimit) ? x : u32x4{0u, 0u, 0u, 0u};
-      }
+      for (int ks = 0; ks < KS; ++ks) kf[kt][ks] = *(const u32x4*)(kp + 32 * ks);
     }
 #pragma unroll
     for (int it = 0; it < NVC; ++it) {
       const int c = lane + 64 * it, key = kbase + c / DC, dc = c % DC;
-      const u32x4 x = *(const u32x4*)(vsrc + (int64_t)min(key, last) * pitch + 8 * dc);
-      vr[it] = (t < nt && key < klimit) ? x : u32x4{0u, 0u, 0u, 0u};
+      vr[it] = *(const u32x4*)(vsrc + (int64_t)min(key, last) * pitch + 8 * dc);
     }
   };
-  const bool has_keys = P > 0 || T > 0;   // T >= 1 for a row that reaches this point
-  if (wave < nt && has_keys) request_tile(wave);
-
   for (int i = tid; i < T; i += NT) {
     int pi = p.parent[lo + i];
     if (pi >= i || pi < -1 || (i == 0 && pi != -1) || (i > 0 && pi < 0)) {
@@ -813,6 +810,10 @@ __global__ __launch_bounds__(512) void attn_bf16_qsplit_kernel(AttnParams p) {
       else qf[ks].u = make_uint4(0, 0, 0, 0);
     }
   }
+  // The first tile is requested AFTER the parent and query loads: loads return in order, so the wait
+  // for the parent entry below then leaves the 32 tile loads in flight instead of draining them.
+  const bool has_keys = P > 0 || T > 0;   // T >= 1 for a row that reaches this point
+  if (wave < nt && has_keys) request_tile(wave);
   __syncthreads();   // parent array complete
   if (tid < 32) {
     // ancestor-or-self bits of the (at most two) tree tiles for the 16 query rows
@@ -840,14 +841,7 @@ __global__ __launch_bounds__(512) void attn_bf16_qsplit_kernel(AttnParams p) {
     const bool tree_tile = t >= n_pt;
     const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
     const int klimit = tree_tile ? T : P;
-    // V: registers -> this wave's LDS tile (row-major); the previous tile's reads are complete (same wave, in order)
-#pragma unroll
-    for (int it = 0; it < NVC; ++it) {
-      const int c = lane + 64 * it;
-      *(u32x4*)(&vt[(c / DC) * VP + 8 * (c % DC)]) = vr[it];
-    }
-    __builtin_amdgcn_wave_barrier();   // keep the tile's stores ahead of its transposing reads in program order
-    // S^T = K Q^T from the register fragments
+    // S^T = K Q^T from the register fragments (K was requested before V and arrives first)
     f32x4 st[4];
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
@@ -859,6 +853,14 @@ __global__ __launch_bounds__(512) void attn_bf16_qsplit_kernel(AttnParams p) {
         st[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8.v, qf[ks].v, st[kt], 0, 0, 0);
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
+    // V: registers -> this wave's LDS tile (row-major); the previous tile's reads are complete (same wave, in order)
+#pragma unroll
+    for (int it = 0; it < NVC; ++it) {
+      const int c = lane + 64 * it;
+      *(u32x4*)(&vt[(c / DC) * VP + 8 * (c % DC)]) = vr[it];
+    }
+    __builtin_amdgcn_wave_barrier();   // keep the tile's stores ahead of its transposing reads in program order
     if (t + NWV < nt) request_tile(t + NWV);   // next tile of this wave streams in during the softmax
 
     unsigned long long valid;
