@@ -75,6 +75,24 @@ __device__ __forceinline__ f32x4 gram_tile(const uint16_t* rowa, const uint16_t*
   return acc;
 }
 
+// The same Gram tile of one row set with itself over NS k-steps, all of the lane's NS 16-byte pieces
+// requested before the first multiplication (one round trip instead of NS / 4), side() issued
+// behind them (loads return in order, so what side() requests arrives after the rows), four
+// independent accumulator chains.
+template <int NS, typename F>
+__device__ __forceinline__ f32x4 gram_tile_deep(const uint16_t* row, int k0, int g, F&& side) {
+  Frag8 f[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) f[s].u = *(const uint4*)(row + k0 + 32 * s + 8 * g);
+  side();
+  f32x4 acc[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < NS; ++s) acc[s & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[s].v, f[s].v, acc[s & 3], 0, 0, 0);
+  return (acc[0] + acc[1]) + (acc[2] + acc[3]);
+}
+
 // a . x and x . x in one pass (generic rows)
 __device__ __forceinline__ void dot2_rows(const float* a, const float* x, int h, int lane, float& ax, float& xx) {
   float s = 0.f, t = 0.f;
@@ -188,10 +206,13 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
   int my_tok = -1;
   if (own_sib) my_tok = a.token[lo + s_sib[tid]];
   else if (own_ch) my_tok = a.token[lo + s_chl[tid - 64]];
-  float my_q = 0.f;
-  auto gather_q = [&]() {
-    if ((own_sib || own_ch) && my_tok >= 0 && my_tok < a.vocab) my_q = prob_of(Lp, thr, lse, my_tok);
+  float my_q = 0.f, my_logit = -INFINITY;
+  const bool q_wanted = (own_sib || own_ch) && my_tok >= 0 && my_tok < a.vocab;
+  auto request_q = [&]() {   // the load only; its value is turned into a probability later
+    if (q_wanted) my_logit = Lp[my_tok];
   };
+  auto finish_q = [&]() { my_q = (q_wanted && my_logit >= thr) ? __expf(my_logit - lse) : 0.f; };
+  auto gather_q = [&]() { request_q(); finish_q(); };
 
   const T* row_a = H + (int64_t)gi * h;
   bool mfma_done = false;
@@ -205,8 +226,14 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
         const int o = 15 * blk + l16 - 1;
         const uint16_t* ra = l16 == 0 ? (const uint16_t*)row_a
                                       : (const uint16_t*)(H + (int64_t)(lo + s_other[min(o, n_other - 1)]) * h);
-        const f32x4 acc = gram_tile(ra, ra, true, wave * kq, (wave + 1) * kq, g);
-        if (blk == 0) gather_q();
+        f32x4 acc;
+        if (kq == 1024) {   // hidden = 4096: the whole quarter row in flight at once
+          acc = gram_tile_deep<32>(ra, wave * kq, g, [&]() { if (blk == 0) request_q(); });
+          if (blk == 0) finish_q();
+        } else {
+          acc = gram_tile(ra, ra, true, wave * kq, (wave + 1) * kq, g);
+          if (blk == 0) gather_q();
+        }
         if (blk > 0) __syncthreads();   // the previous block's partial tiles have been consumed
 #pragma unroll
         for (int r = 0; r < 4; ++r) gq[wave][(4 * g + r) * 16 + l16] = acc[r];
