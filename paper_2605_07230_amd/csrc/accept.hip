@@ -139,6 +139,13 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
   const int lo = a.node_off[b], Tn = a.node_off[b + 1] - lo;
   if (node >= Tn) return;
   const int64_t gi = lo + node;
+  // wave 0 scans the tree for siblings and children; its first chunk (parents and tokens of nodes
+  // 0..63) is requested here, before anything waits for this node's own parent pointer
+  int pj0 = -2, tk0 = -1;
+  if (wave == 0 && lane < Tn) {
+    pj0 = a.parent[lo + lane];
+    tk0 = a.token[lo + lane];
+  }
   const int par = a.parent[gi];
   auto write_zero = [&]() {
     if (tid == 0) {
@@ -160,13 +167,18 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
     int ks = 0, kc = 0, rank = -1;
     for (int base = 0; base < Tn; base += 64) {   // from chunk 0: these loads do not wait for par
       const int j = base + lane;
-      const int pj = j < Tn ? a.parent[lo + j] : -2;
+      int pj = pj0, tk = tk0;
+      if (base > 0) {
+        pj = j < Tn ? a.parent[lo + j] : -2;
+        tk = j < Tn ? a.token[lo + j] : -1;
+      }
       const bool sib = pj == par && j > par;
       const unsigned long long sm = __ballot(sib);
       if (sib) {
         const int r = ks + __popcll(sm & ((1ull << lane) - 1ull));
         if (r < MAXW) {
           s_sib[r] = j;
+          s_stok[r] = tk;
           // other index: parent is 0; siblings keep their rank order with a left out
           if (j != node) s_other[1 + r - (j > node ? 1 : 0)] = j;
         }
@@ -177,7 +189,7 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
       const unsigned long long cm = __ballot(ch);
       if (ch) {
         const int r = kc + __popcll(cm & ((1ull << lane) - 1ull));
-        if (r < MAXW) s_chl[r] = j;
+        if (r < MAXW) { s_chl[r] = j; s_ctok[r] = tk; }
       }
       kc += __popcll(cm);
     }
@@ -200,12 +212,12 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
   if (tid < kc) s_other[1 + n_sib + tid] = s_chl[tid];   // the children come after the siblings
   __syncthreads();
 
-  // tokens of the siblings (threads 0 .. ks-1) and of the children (threads 64 .. 64+kc-1): requested now,
-  // their probabilities under the parent's distribution gathered while the feature rows are in flight
+  // tokens of the siblings (threads 0 .. ks-1) and of the children (threads 64 .. 64+kc-1), left in LDS by
+  // the scan; their probabilities under the parent's distribution are gathered while the feature rows are in flight
   const bool own_sib = tid < ks, own_ch = tid >= 64 && tid < 64 + kc;
   int my_tok = -1;
-  if (own_sib) my_tok = a.token[lo + s_sib[tid]];
-  else if (own_ch) my_tok = a.token[lo + s_chl[tid - 64]];
+  if (own_sib) my_tok = s_stok[tid];
+  else if (own_ch) my_tok = s_ctok[tid - 64];
   float my_q = 0.f, my_logit = -INFINITY;
   const bool q_wanted = (own_sib || own_ch) && my_tok >= 0 && my_tok < a.vocab;
   auto request_q = [&]() {   // the load only; its value is turned into a probability later
