@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the read counter sees half of the bytes that 16-byte-per-lane loads move (factor 2.0), writes
 # count 1.0.  The summaries are profiles/*_pmc.md; None where no counter run exists.
 MEASURED_TRAFFIC_BYTES = {
-    ("janus_pro_7b", "lmhead"): int((69763.0 * 2.0 + 3840.0) * 1024),
+    ("janus_pro_7b", "lmhead"): int((69952.5 * 2.0 + 3840.0) * 1024),
 }
 
 
