@@ -203,6 +203,35 @@ def test_rows_with_outliers():
     assert (kept >= 300).all() and (kept <= 310).all()
 
 
+@pytest.mark.parametrize("case", ["plain", "ragged_vocab", "all_equal_row", "ties_at_threshold", "huge_k", "outliers"])
+def test_row_statistics_of_long_rows(case):
+    """Rows of more than 16384 entries take the compacted path (candidates above the first histogram
+    round's bin edge) unless the candidate set is too large; every variant must select exactly the k-th
+    largest of the GPU's own logits."""
+    rng = np.random.default_rng(21)
+    vocab = 65536 - 512 if case == "ragged_vocab" else 65536
+    top_k = 40000 if case == "huge_k" else 2000
+    print(f"[long rows] {case}", flush=True)
+    inp = _small_bf16(21, n_prompts=1, prefix_lens=[8, 8], trees=[wl.grow_tree(rng, 10, 3, 4)], hidden=128, vocab=vocab,
+                      top_k=top_k, align=0.0)
+    if case == "all_equal_row":
+        inp.h_cond[2] = 0.0
+        inp.h_uncond[2] = 0.0
+    if case == "ties_at_threshold":
+        inp.w[1000:9000] = inp.w[1000]          # 8000 identical vocabulary rows: a long run of equal logits in every row
+    if case == "outliers":
+        inp.w[:40] = wl.round_bf16(inp.w[:40] * 60.0)
+    ds = pu.run_gpu_step(inp)
+    pu.check_lmhead(inp, ds)
+    g = ds.logits.cpu().numpy()
+    kept = (g >= ds.row_thr.cpu().numpy()[:, None]).sum(axis=1)
+    assert (kept >= top_k).all()
+    if case in ("plain", "ragged_vocab", "outliers"):
+        assert (kept <= top_k + 64).all()
+    if case == "all_equal_row":
+        assert kept[2] == vocab
+
+
 def test_f32_ragged_batch():
     rng = np.random.default_rng(4)
     inp = _small_bf16(4, dtype="f32", head_dim=32, hidden=96, vocab=300, top_k=20,
