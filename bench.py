@@ -285,7 +285,7 @@ def main() -> int:
         del feats
 
     # chained steps through the KV commit until a whole image is formed (context only: synthetic
-    # step inputs cycled from a pool; the host reads the accepted length back after every step)
+    # step inputs cycled from a pool; timed once with a stream wait per step and once pipelined)
     loop_out = None
     if args.decode_image > 0 and inp.n_prompts == 1:
         from paper_2605_07230_amd import decode
@@ -295,10 +295,15 @@ def main() -> int:
         loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed)
         loop.run(max_steps=5)                           # warm-up
         loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed)
-        lr = loop.run()
+        lr_sync = loop.run()                            # one stream wait per step
+        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed)
+        lr = loop.run_pipelined()                       # accepted lengths read back two steps late
+        assert lr.accept_lens == lr_sync.accept_lens and lr.emitted == lr_sync.emitted
         loop_out = {"image_tokens": args.decode_image, "steps": lr.steps, "tokens": lr.tokens,
                     "mean_accept_len": lr.mean_accept_len, "tvd_per_image": lr.tvd_per_image,
-                    "ms_per_image": lr.seconds * 1e3, "ms_per_step": lr.seconds * 1e3 / max(lr.steps, 1)}
+                    "ms_per_image": lr.seconds * 1e3, "ms_per_step": lr.seconds * 1e3 / max(lr.steps, 1),
+                    "ms_per_image_synchronous": lr_sync.seconds * 1e3,
+                    "ms_per_step_synchronous": lr_sync.seconds * 1e3 / max(lr_sync.steps, 1)}
         del loop
 
     # what this device sustains: a plain streaming read of 1 GiB and a register-only MFMA loop

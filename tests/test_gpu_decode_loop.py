@@ -66,3 +66,23 @@ def test_decode_loop_tiny_f32():
 def test_decode_loop_janus_shaped():
     res = _chain_check(1, [0, 2], 8)
     assert res.steps >= 2
+
+
+@pytest.mark.parametrize("config,seeds,image_tokens", [(0, [0, 1, 3, 7], 40), (1, [0, 2, 5], 24)])
+def test_pipelined_loop_equals_the_synchronous_one(config, seeds, image_tokens):
+    """Reading the accepted lengths back two steps late changes nothing that is reported: same steps,
+    same accepted lengths, same emitted tokens, same budget use; the cache agrees on every position the
+    synchronous loop wrote (the pipelined loop may have committed up to two discarded steps beyond)."""
+    from paper_2605_07230_amd import decode
+    pool = [wl.make_config(config, s) for s in seeds]
+    for p in pool[1:]:
+        p.w = pool[0].w
+    print(f"[pipelined loop] {pool[0].name} seeds={seeds}", flush=True)
+    a = decode.DecodeLoop(pool, image_tokens, packed_w=pool[0].dtype == "bf16")
+    ra = a.run()
+    b = decode.DecodeLoop(pool, image_tokens, packed_w=pool[0].dtype == "bf16")
+    rb = b.run_pipelined()
+    assert ra.steps == rb.steps and ra.tokens == rb.tokens
+    assert ra.accept_lens == rb.accept_lens and ra.emitted == rb.emitted and ra.tvd_used == rb.tvd_used
+    n = int(a.prefix_len.max().item())
+    assert torch.equal(a.k_cache[..., :n, :], b.k_cache[..., :n, :]) and torch.equal(a.v_cache[..., :n, :], b.v_cache[..., :n, :])
