@@ -119,6 +119,24 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnParams p, int n_rows,
 // ----------------------------------------------------------------------------------------- bf16
 constexpr int KT = 64;  // keys per tile
 
+// Workgroups are dispatched in index order, and with ragged prefixes the rows differ several-fold in
+// work: a heavy row that happens to sit at the end of the batch would start when the rest of the grid
+// is almost done and finish alone.  Dispatch position z therefore takes the z-th heaviest row
+// (keys = prefix + tree nodes; ties by index), computed redundantly by every wave from the two small
+// arrays it reads anyway.  Batches of more than 64 rows keep their order.
+__device__ __forceinline__ int row_by_work_rank(const AttnParams& p, int z, int n_rows, int lane) {
+  if (n_rows > 64 || n_rows <= 1) return z;
+  int work = -1;
+  if (lane < n_rows) work = p.prefix_len[lane] + (p.node_off[lane + 1] - p.node_off[lane]);
+  int rank = 0;
+  for (int r = 0; r < n_rows; ++r) {
+    const int wr = __builtin_amdgcn_readlane(work, r);
+    rank += (wr > work || (wr == work && r < lane)) ? 1 : 0;
+  }
+  const unsigned long long hit = __ballot(lane < n_rows && rank == z);
+  return hit ? __ffsll((long long)hit) - 1 : z;
+}
+
 // Workgroups are dealt round-robin to the 8 XCDs (one L2 each) in launch order: hardware id h runs on
 // XCD h % 8.  A unit = the nx workgroups of one (row, kv head).  This renumbering keeps a unit's
 // workgroups on one XCD (they meet in one L2) while consecutive units still go to different XCDs, so
@@ -181,7 +199,8 @@ __global__ __launch_bounds__(64 * NW, (NQ == 4 || NW == 8) ? 1 : 2) void attn_bf
   // the query blocks and splits of a (row, kv head), which stream the same keys and values, share an L2
   const unsigned nx = gridDim.x, ny = gridDim.y;
   const unsigned lid = xcd_local_order(blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z), nx, ny * gridDim.z);
-  const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny), s = (int)(lid / (nx * ny));
+  const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny);
+  const int s = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, threadIdx.x & 63);
   const int split = bx % p.n_split, sb = bx / p.n_split;
   const int lo = p.node_off[s];
   const int T = p.node_off[s + 1] - lo;
@@ -451,7 +470,8 @@ struct KsplitGroupSmem {
 
 // NKG = key groups (the workgroup has NKG * 4 waves)
 template <int D, int NKG, bool SPLIT>
-__global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams p) {
+// (four waves per workgroup: at most 168 registers, so that three workgroups share a CU)
+__global__ __launch_bounds__(NKG * 256, (NKG == 1 ? 3 : 1)) void attn_bf16_ksplit_kernel(AttnParams p) {
   constexpr int NT = NKG * 256;
   using GS = KsplitGroupSmem<D>;
   extern __shared__ __align__(16) char smem_raw[];
@@ -468,7 +488,8 @@ __global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams 
   // the query blocks and splits of a (row, kv head) share an L2
   const unsigned nx = gridDim.x, ny = gridDim.y;
   const unsigned lid = xcd_local_order(blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z), nx, ny * gridDim.z);
-  const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny), s = (int)(lid / (nx * ny));
+  const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny);
+  const int s = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, threadIdx.x & 63);
   const int split = bx % p.n_split, sb = bx / p.n_split;
   const int lo = p.node_off[s];
   const int T = p.node_off[s + 1] - lo;
@@ -488,24 +509,29 @@ __global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams 
   const uint16_t* vtr = (const uint16_t*)p.v_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D;
   const int64_t tree_pitch = (int64_t)p.n_kv_heads * D;
 
-  // a quarter of the group's tile per wave: pieces gl, gl + 256, ... (piece c = key c / DC, 8 d at c % DC)
+  // a quarter of the group's tile per wave: pieces gl, gl + 256, ... (piece c = key c / DC, 8 d at c % DC),
+  // requested one round ahead (two rounds ahead, with a second register set, changed nothing).  Keys
+  // past the end of the tile's source are read from its last row (clamped: always in bounds) and not
+  // zeroed: their scores are masked to -inf, so their probabilities are exactly 0 and the clamped
+  // (finite) rows contribute nothing; a select or a branch on the loaded value would make the compiler
+  // wait for every load on the spot.
   uint4 kr[NPC], vr[NPC];
+#pragma unroll
+  for (int it = 0; it < NPC; ++it) kr[it] = vr[it] = make_uint4(0, 0, 0, 0);
   auto request_tile = [&](int t) {
+    if (t >= t_end) return;   // uniform per wave
     const bool tree_tile = t >= n_pt;
     const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
-    const int klimit = tree_tile ? T : P;
+    const int last = (tree_tile ? T : P) - 1;   // >= 0: a tile exists only if its source has keys
     const uint16_t* ksrc = tree_tile ? ktr : kc;
     const uint16_t* vsrc = tree_tile ? vtr : vc;
     const int64_t pitch = tree_tile ? tree_pitch : p.sp;
 #pragma unroll
     for (int it = 0; it < NPC; ++it) {
       const int c = gl + 256 * it, key = c / DC, dc = c % DC;
-      kr[it] = make_uint4(0, 0, 0, 0);
-      vr[it] = make_uint4(0, 0, 0, 0);
-      if (t < t_end && kbase + key < klimit) {
-        kr[it] = *(const uint4*)(ksrc + (int64_t)(kbase + key) * pitch + 8 * dc);
-        vr[it] = *(const uint4*)(vsrc + (int64_t)(kbase + key) * pitch + 8 * dc);
-      }
+      const int64_t o = (int64_t)min(kbase + key, last) * pitch + 8 * dc;
+      kr[it] = *(const uint4*)(ksrc + o);
+      vr[it] = *(const uint4*)(vsrc + o);
     }
   };
   request_tile(t_begin + kg);   // first round's tile: in flight while queries and parents are fetched
@@ -567,7 +593,7 @@ __global__ __launch_bounds__(NKG * 256) void attn_bf16_ksplit_kernel(AttnParams 
       }
       s_anc[lane] = wbits;
     }
-    if (r + 1 < n_rounds) request_tile(t + NKG);   // next round streams in while this one is consumed
+    request_tile(t + NKG);   // next round streams in while this one is consumed
     __syncthreads();
     if (!active) continue;
 
