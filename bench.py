@@ -68,7 +68,7 @@ def cpu_baseline(inp, budget_s: float = 12.0):
         vo.verify_step(inp)
         n += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or n >= 20:
+        if el >= budget_s or n >= 200:
             break
     return {"value": n / el, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{n} whole step(s) of the same workload (numpy float64; BLAS threads = cores), {el:.1f} s"}
