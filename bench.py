@@ -2,7 +2,11 @@
 """Benchmark of the MI355X tree-verification step (one GPU).
 
 A step = tree_verify_attn + lmhead_softmax_cfg + cascade_accept + select_path over one batch of
-synthetic input that is already resident in HBM.  Prints ONE JSON line.
+synthetic input that is already resident in HBM.  Prints ONE JSON line.  The headline is the stress
+configuration (the largest one: 4 prompts x 2 guidance rows, 4200-key prefix, 256-node trees,
+vocabulary 65536), the shape on which the roofline targets mean something: the projection is bound
+by the matrix cores, attention and the row statistics by HBM.  The smaller configurations are timed
+in the same run and reported as a nested block.
 
 The large read-only inputs (LM-head matrix, KV cache) are rotated over several independent copies
 so that consecutive steps cannot be served from the 256 MB Infinity Cache: in a real decode loop a
@@ -23,13 +27,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs of this file (FETCH_SIZE and
-# WRITE_SIZE, KiB per dispatch), scaled by what the same counters report for a copy of known size:
-# the read counter sees half of the bytes that 16-byte-per-lane loads move (factor 2.0), writes
-# count 1.0.  The summaries are profiles/*_pmc.md; None where no counter run exists.
-MEASURED_TRAFFIC_BYTES = {
-    ("janus_pro_7b", "lmhead"): int((69952.5 * 2.0 + 3840.0) * 1024),
+# HBM traffic per launch from rocprofv3 --pmc runs of this file: (FETCH_SIZE, WRITE_SIZE) in KiB per
+# dispatch, copied from the tracked counter summaries (a CPU test compares this table with the
+# "TRAFFIC" lines of those summaries).  Bytes = FETCH x 2.0 + WRITE x 1.0: the read counter sees half
+# of the bytes that 16-byte-per-lane loads move, as the same counter shows for a streaming read of
+# known size in the same runs; writes count 1.0.  No entry = no counter run = traffic null.
+FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
+MEASURED_TRAFFIC_KIB = {
+    ("janus_pro_7b", "lmhead"): (69916.2, 3840.0),
+    ("janus_pro_7b", "attn"): (6516.0, 1080.0),
+    ("janus_pro_7b", "row_stats"): (1981.0, 5.6),
+    ("janus_pro_7b", "accept"): (974.7, 11.2),
 }
+
+
+def measured_traffic(workload: str, kernel: str):
+    kib = MEASURED_TRAFFIC_KIB.get((workload, kernel))
+    return None if kib is None else int((kib[0] * FETCH_FACTOR + kib[1] * WRITE_FACTOR) * 1024)
 
 
 def algorithmic_bytes_lmhead(inp) -> int:
@@ -55,8 +69,20 @@ def algorithmic_bytes_attn(inp) -> int:
     return total
 
 
+def algorithmic_bytes_row_stats(inp) -> int:
+    """The mixed logits once (row max, k-th largest and log-sum-exp need every entry) + three scalars out."""
+    return inp.n_nodes * inp.vocab * 4 + inp.n_nodes * 12
+
+
+def algorithmic_bytes_accept(inp) -> int:
+    """Every node's hidden state once + the six per-node scalars out (token-probability gathers are a few bytes per node)."""
+    e = 2 if inp.dtype == "bf16" else 4
+    return inp.n_nodes * inp.hidden * e + inp.n_nodes * 24
+
+
 def cpu_baseline(inp, budget_s: float = 12.0):
-    """The CPU checker, as it stands, on the same workload; whole steps until the budget is used."""
+    """The CPU checker, as it stands, on the same workload; whole steps until the budget is used
+    (at least one: a stress-shaped step takes about 20 s)."""
     from oracle import verify_oracle as vo
     try:
         from threadpoolctl import threadpool_info
@@ -147,19 +173,150 @@ def tau_sweep(args) -> int:
     return 0
 
 
+KERNEL_NAMES = {0: "attn", 1: "attn_merge", 2: "lmhead", 3: "row_stats", 4: "accept", 5: "select", 8: "pack_h"}
+
+
+def measure_workload(index: int, steps: int, warmup: int, args, hbm_meas: float, mfma_meas: float):
+    """Times `steps` whole steps of one configuration (wall clock), then the same steps again with the
+    library's per-kernel events on; returns (inputs, device step, dict for the JSON line)."""
+    import torch
+    from paper_2605_07230_amd import binding, workloads as wl
+    inp = wl.make_config(index, args.seed)
+    ds = binding.DeviceStep(inp)
+    copies = max(1, args.copies)
+    # weights are repacked once into MFMA operand order, as at model load (outside the timed region)
+    packed = inp.dtype == "bf16" and not args.row_major_w
+    layout = binding.W_PACKED32 if packed else binding.W_ROWMAJOR
+    w0 = ds.pack_w() if packed else ds.w
+    ws = [w0] + [w0.clone() for _ in range(copies - 1)]
+    kcs = [ds.k_cache] + [ds.k_cache.clone() for _ in range(copies - 1)]
+    vcs = [ds.v_cache] + [ds.v_cache.clone() for _ in range(copies - 1)]
+
+    def step(i: int) -> None:
+        j = i % copies
+        ds.k_cache, ds.v_cache = kcs[j], vcs[j]
+        ds.step(w=ws[j], w_layout=layout)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert ds.ctx.device_status() == binding.OK
+
+    # the same steps on ONE copy of the inputs (W and KV stay in the 256 MB last-level cache where they fit): context only
+    ms_cache_warm = None
+    if args.cache_warm:
+        n_warm = min(steps, 200)
+        for i in range(10):
+            step(0)
+        torch.cuda.synchronize()
+        tw = time.perf_counter()
+        for i in range(n_warm):
+            step(0)
+        torch.cuda.synchronize()
+        ms_cache_warm = (time.perf_counter() - tw) * 1e3 / n_warm
+
+    # second pass over the same steps with the dispatch's own begin / end timestamps on every launch
+    # (HIP events on the library's stream, handed to the launch itself)
+    ds.ctx.set_kernel_timing(True)
+    n_timed = min(steps, 2000)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(n_timed):
+        step(i)
+    torch.cuda.synchronize()
+    ms_events = (time.perf_counter() - t1) * 1e3 / n_timed
+    kernel_us = {}
+    for kid, name in KERNEL_NAMES.items():
+        ms, n = ds.ctx.read_kernel_timing(kid)
+        if n:
+            kernel_us[name] = ms * 1e3 / n
+    ds.ctx.set_kernel_timing(False)
+
+    rows = inp.n_nodes * (2 if inp.h_uncond is not None else 1)
+    tiled = packed and rows >= 512 and inp.vocab % 256 == 0
+    # projection: bound by the matrix cores when the step has several hundred rows, by the W stream otherwise
+    if tiled:
+        flops = algorithmic_flops_lmhead(inp)
+        ach = flops / (kernel_us["lmhead"] * 1e-6) / 1e12
+        roof_lm = {"kernel": "lmhead_bf16_tiled_kernel", "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                   "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(inp.name, "lmhead"),
+                   "algorithmic_flops": flops, "algorithmic_bytes": algorithmic_bytes_lmhead(inp),
+                   "frac_of_measured_peak": ach / mfma_meas}
+    else:
+        nbytes = algorithmic_bytes_lmhead(inp)
+        ach = nbytes / (kernel_us["lmhead"] * 1e-6) / 1e9
+        kname = "lmhead_f32_kernel" if inp.dtype == "f32" else ("lmhead_bf16_packed_kernel" if packed else "lmhead_bf16_kernel")
+        roof_lm = {"kernel": kname, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                   "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(inp.name, "lmhead"), "algorithmic_bytes": nbytes,
+                   "frac_of_measured_peak": ach / hbm_meas}
+    roof_lm["avg_launch_us"] = kernel_us["lmhead"]
+
+    def hbm_block(kernel, nbytes, us, traffic):
+        ach = nbytes / (us * 1e-6) / 1e9
+        return {"kernel": kernel, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes": nbytes,
+                "frac_of_measured_peak": ach / hbm_meas, "avg_launch_us": us}
+
+    max_tree = int((inp.node_off[1:] - inp.node_off[:-1]).max())
+    m_rows = max_tree * (inp.n_heads // inp.n_kv_heads)
+    units = inp.n_rows * inp.n_kv_heads * ((m_rows + 63) // 64)
+    if inp.dtype == "f32":
+        attn_kernel = "attn_f32_kernel"
+    elif m_rows > 128:
+        attn_kernel = "attn_bf16_kernel"
+    else:
+        attn_kernel = "attn_bf16_qsplit_kernel" if units <= 128 else "attn_bf16_ksplit_kernel"
+    attn_us = kernel_us.get("attn", 0.0) + kernel_us.get("attn_merge", 0.0)
+    t_attn, t_merge = measured_traffic(inp.name, "attn"), measured_traffic(inp.name, "attn_merge")
+    if t_attn is not None and "attn_merge" in kernel_us:
+        t_attn = None if t_merge is None else t_attn + t_merge
+    roof_attn = hbm_block(attn_kernel + (" + attn_merge_kernel" if "attn_merge" in kernel_us else ""),
+                          algorithmic_bytes_attn(inp), attn_us, t_attn)
+    roof_stats = hbm_block("row_stats_kernel", algorithmic_bytes_row_stats(inp), kernel_us["row_stats"],
+                           measured_traffic(inp.name, "row_stats"))
+    # attention + everything that turns logits into an accepted path (row statistics, acceptance scalars, walk)
+    acc_bytes = algorithmic_bytes_attn(inp) + algorithmic_bytes_row_stats(inp) + algorithmic_bytes_accept(inp)
+    acc_us = attn_us + kernel_us["row_stats"] + kernel_us["accept"] + kernel_us["select"]
+    parts = [measured_traffic(inp.name, k) for k in ("row_stats", "accept", "select")] + [t_attn]
+    roof_acc = hbm_block("attention + row statistics + acceptance + walk", acc_bytes, acc_us,
+                         None if any(x is None for x in parts) else sum(parts))
+
+    out = {
+        "workload": inp.name, "steps": steps, "warmup": warmup, "ms_per_step": elapsed * 1e3 / steps,
+        "steps_per_s": steps / elapsed, "tree_nodes_per_s": inp.n_nodes * steps / elapsed,
+        "ms_per_step_with_events": ms_events, "ms_per_step_cache_warm": ms_cache_warm,
+        "kernel_us": kernel_us, "accept_len": ds.accept_len.cpu().tolist(),
+        "roofline": roof_lm, "roofline_attention": roof_attn, "roofline_row_stats": roof_stats,
+        "roofline_attn_accept": roof_acc,
+        "config": {"workload": inp.name, "rows": inp.n_rows, "prompts": inp.n_prompts, "tree_nodes": inp.n_nodes,
+                   "prefix_len": int(inp.prefix_len.max()), "heads": inp.n_heads, "head_dim": inp.head_dim,
+                   "hidden": inp.hidden, "vocab": inp.vocab, "cfg_scale": inp.cfg_scale, "top_k": inp.top_k,
+                   "input_copies_rotated": copies, "lmhead_w_layout": "packed32" if packed else "row_major"},
+    }
+    del ws, kcs, vcs
+    return inp, ds, out, packed
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", type=int, default=1, help="index into the five configurations (default 1: Janus-Pro-7B-shaped)")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=4, help="index into the five configurations (default 4: the stress configuration)")
+    ap.add_argument("--others", type=str, default="1,2,3", help="configurations also timed and reported in the nested block ('' = none)")
+    ap.add_argument("--other-steps", type=int, default=200)
     ap.add_argument("--copies", type=int, default=4, help="independent copies of W / KV rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--row-major-w", action="store_true", help="keep the LM-head matrix row-major (default: packed once, as at model load)")
     ap.add_argument("--cache-warm", action="store_true", help="also time the steps on one copy of the inputs (served from the last-level cache)")
     ap.add_argument("--commit-layers", type=int, default=30, help="decoder layers in the separately timed KV commit (0: skip)")
     ap.add_argument("--weights-seqs", type=int, default=8, help="sequences in the separately timed Eq. 4 weight mask (0: skip)")
-    ap.add_argument("--decode-image", type=int, default=0, help="tokens of the separately timed multi-step decode loop (0: skip)")
+    ap.add_argument("--decode-image", type=int, default=0, help="tokens of the separately timed multi-step decode loop (0: skip; single-prompt workloads)")
     ap.add_argument("--tau-sweep", action="store_true", help="instead of the step benchmark: threshold sweep on stress-shaped trees")
     ap.add_argument("--sweep-seeds", type=int, default=32)
     ap.add_argument("--rank-zipf", action="store_true", help="tau sweep: re-draw draft tokens by Zipf rank of the parent's logits")
@@ -179,88 +336,43 @@ def main() -> int:
     binding.load_library()
     torch.cuda.set_device(0)
 
-    inp = wl.make_config(args.workload, args.seed)
-    ds = binding.DeviceStep(inp)
-    copies = max(1, args.copies)
-    # weights are repacked once into MFMA operand order, as at model load (outside the timed region)
-    packed = inp.dtype == "bf16" and not args.row_major_w
-    layout = binding.W_PACKED32 if packed else binding.W_ROWMAJOR
-    w0 = ds.pack_w() if packed else ds.w
-    ws = [w0] + [w0.clone() for _ in range(copies - 1)]
-    kcs = [ds.k_cache] + [ds.k_cache.clone() for _ in range(copies - 1)]
-    vcs = [ds.v_cache] + [ds.v_cache.clone() for _ in range(copies - 1)]
+    # what this device sustains: a plain streaming read of 1 GiB and a register-only MFMA loop
+    cal = binding.Context(max_rows=1, max_nodes_total=1, max_nodes_per_tree=1, max_prefix=1, n_heads=1, head_dim=64, hidden=128, vocab=64)
+    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    big.zero_()
+    hbm_meas = cal.measure_hbm_read(big, 5)
+    mfma_meas = cal.measure_mfma_bf16(8192)
+    del big
+    cal.close()
 
-    def step(i: int) -> None:
-        j = i % copies
-        ds.k_cache, ds.v_cache = kcs[j], vcs[j]
-        ds.step(w=ws[j], w_layout=layout)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    assert ds.ctx.device_status() == binding.OK
-
-    # the same steps on ONE copy of the inputs (W and KV stay in the 256 MB last-level cache): context only
-    # (off by default so that a profile of the default command averages HBM-fed launches only)
-    ms_per_step_cache_warm = None
-    if args.cache_warm:
-        n_warm = min(args.steps, 200)
-        for i in range(10):
-            step(0)
-        torch.cuda.synchronize()
-        tw = time.perf_counter()
-        for i in range(n_warm):
-            step(0)
-        torch.cuda.synchronize()
-        ms_per_step_cache_warm = (time.perf_counter() - tw) * 1e3 / n_warm
-
-    # second pass with HIP events around every kernel launch (on the library's stream)
-    ds.ctx.set_kernel_timing(True)
-    n_timed = min(args.steps, 2000)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for i in range(n_timed):
-        step(i)
-    torch.cuda.synchronize()
-    ms_per_step_events = (time.perf_counter() - t1) * 1e3 / n_timed
-    names = {0: "attn", 1: "attn_merge", 2: "lmhead", 3: "row_stats", 4: "accept", 5: "select", 8: "pack_h"}
-    kernel_us = {}
-    for kid, name in names.items():
-        ms, n = ds.ctx.read_kernel_timing(kid)
-        if n:
-            kernel_us[name] = ms * 1e3 / n
-    ds.ctx.set_kernel_timing(False)
+    print(f"[bench] headline workload {args.workload}", file=sys.stderr, flush=True)
+    inp, ds, head, packed = measure_workload(args.workload, args.steps, args.warmup, args, hbm_meas, mfma_meas)
 
     # the KV commit that follows the step (not part of the step metric): all decoder layers' worth of
     # tree keys / values, the path the step just chose, appended to a cache with room
     commit = None
     if args.commit_layers > 0:
         Lc, S, Hkv, D = args.commit_layers, inp.n_rows, inp.n_kv_heads, inp.head_dim
-        cap = inp.prefix_cap + inp.max_depth + 4
+        cap = inp.max_depth + 8          # room for root + path; the prefix itself is not touched by the commit
         dt = ds.k_tree.dtype
         kt = torch.randn((Lc, ds.k_tree.shape[0], Hkv, D), device="cuda").to(dt)
         vt = torch.randn((Lc, ds.k_tree.shape[0], Hkv, D), device="cuda").to(dt)
         kc = torch.zeros((Lc, S, Hkv, cap, D), dtype=dt, device="cuda")
         vc = torch.zeros((Lc, S, Hkv, cap, D), dtype=dt, device="cuda")
         row_prompt = (torch.arange(S, device="cuda", dtype=torch.int32) // (2 if inp.cfg else 1)).to(torch.int32)
+        plen0 = torch.zeros_like(ds.prefix_len)
         plen_out = torch.empty_like(ds.prefix_len)
         ds.ctx.set_kernel_timing(True)
         for i in range(60):
             binding.kv_commit(ds.ctx, node_off=ds.row_node_off, row_prompt=row_prompt, accept_len=ds.accept_len,
                               path_nodes=ds.path_nodes, k_tree=kt, v_tree=vt, k_cache=kc, v_cache=vc,
-                              prefix_len=ds.prefix_len, prefix_len_out=plen_out)
+                              prefix_len=plen0, prefix_len_out=plen_out)
             if i == 9:
                 ds.ctx.read_kernel_timing(6)      # drop the warm-up launches
         ms, n = ds.ctx.read_kernel_timing(6)
         ds.ctx.set_kernel_timing(False)
         assert ds.ctx.device_status() == binding.OK
-        moved = int((plen_out - ds.prefix_len).sum().item()) * Lc * Hkv * D * kt.element_size() * 2 * 2   # K and V, read + write
+        moved = int((plen_out - plen0).sum().item()) * Lc * Hkv * D * kt.element_size() * 2 * 2   # K and V, read + write
         commit = {"layers": Lc, "us": ms * 1e3 / n, "bytes": moved, "GBs": moved / (ms * 1e-3 / n) / 1e9}
         del kt, vt, kc, vc
 
@@ -306,64 +418,45 @@ def main() -> int:
                     "ms_per_step_synchronous": lr_sync.seconds * 1e3 / max(lr_sync.steps, 1)}
         del loop
 
-    # what this device sustains: a plain streaming read of 1 GiB and a register-only MFMA loop
-    big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-    big.zero_()
-    hbm_meas = ds.ctx.measure_hbm_read(big, 5)
-    mfma_meas = ds.ctx.measure_mfma_bf16(8192)
-    del big
+    ds.ctx.close()
+    del ds
+    torch.cuda.empty_cache()
 
-    # roofline of the dominant kernel
-    dominant = max(kernel_us, key=kernel_us.get)
-    traffic = MEASURED_TRAFFIC_BYTES.get((inp.name, dominant))
-    if dominant == "lmhead":
-        rows = inp.n_nodes * (2 if inp.h_uncond is not None else 1)
-        if rows >= 300:
-            flops = algorithmic_flops_lmhead(inp)
-            ach = flops / (kernel_us["lmhead"] * 1e-6) / 1e12
-            roof = {"kernel": "lmhead_bf16_tiled_kernel", "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic,
-                    "algorithmic_flops": flops, "frac_of_measured_peak": ach / mfma_meas}
-        else:
-            nbytes = algorithmic_bytes_lmhead(inp)
-            ach = nbytes / (kernel_us["lmhead"] * 1e-6) / 1e9
-            kname = "lmhead_f32_kernel" if inp.dtype == "f32" else ("lmhead_bf16_packed_kernel" if packed else "lmhead_bf16_kernel")
-            roof = {"kernel": kname, "bound": "hbm", "achieved": ach,
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": traffic,
-                    "algorithmic_bytes": nbytes, "frac_of_measured_peak": ach / hbm_meas}
-    else:
-        nbytes = algorithmic_bytes_attn(inp)
-        us = kernel_us.get("attn", 0.0) + kernel_us.get("attn_merge", 0.0)
-        ach = nbytes / (us * 1e-6) / 1e9
-        roof = {"kernel": "attn_f32_kernel" if inp.dtype == "f32" else "attn_bf16_*_kernel", "bound": "hbm", "achieved": ach,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes": nbytes,
-                "frac_of_measured_peak": ach / hbm_meas}
-    roof["avg_launch_us"] = kernel_us[dominant if dominant != "attn_merge" else "attn"]
+    # the other configurations, same protocol, fewer steps
+    others = {}
+    for tok in [t for t in args.others.split(",") if t.strip()]:
+        idx = int(tok)
+        if idx == args.workload:
+            continue
+        print(f"[bench] workload {idx}", file=sys.stderr, flush=True)
+        inp_o, ds_o, res_o, _ = measure_workload(idx, args.other_steps, max(5, args.other_steps // 10), args, hbm_meas, mfma_meas)
+        others[res_o["workload"]] = res_o
+        ds_o.ctx.close()
+        del ds_o, inp_o
+        torch.cuda.empty_cache()
 
     out = {
-        "metric": "tree_verify_steps_per_s", "value": args.steps / elapsed, "unit": "steps/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "metric": "tree_verify_steps_per_s", "value": head["steps_per_s"], "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": inp.dtype, "data": "synthetic",
-        "config": {"workload": inp.name, "rows": inp.n_rows, "prompts": inp.n_prompts, "tree_nodes": inp.n_nodes,
-                   "prefix_len": int(inp.prefix_len.max()), "heads": inp.n_heads, "head_dim": inp.head_dim,
-                   "hidden": inp.hidden, "vocab": inp.vocab, "cfg_scale": inp.cfg_scale, "top_k": inp.top_k,
-                   "input_copies_rotated": copies,
-                   "lmhead_w_layout": "packed32" if packed else "row_major"},
-        "tree_nodes_per_s": inp.n_nodes * args.steps / elapsed,
-        "ms_per_step_with_events": ms_per_step_events,
-        "ms_per_step_cache_warm": ms_per_step_cache_warm,
+        "config": head["config"],
+        "tree_nodes_per_s": head["tree_nodes_per_s"],
+        "ms_per_step_with_events": head["ms_per_step_with_events"],
+        "ms_per_step_cache_warm": head["ms_per_step_cache_warm"],
         "measured_peaks": {"hbm_read_GBs": hbm_meas, "mfma_bf16_TFLOPs": mfma_meas},
-        "kernel_us": kernel_us,
-        "attn_hbm_frac": (algorithmic_bytes_attn(inp) / ((kernel_us.get("attn", 0) + kernel_us.get("attn_merge", 0)) * 1e-6) / 1e9
-                          / HBM_PEAK_GBS) if kernel_us.get("attn") else None,
-        "accept_len": ds.accept_len.cpu().tolist(),
+        "kernel_us": head["kernel_us"],
+        "accept_len": head["accept_len"],
         "kv_commit": commit,
         "convergence_weights": weights,
         "decode_loop": loop_out,
-        "roofline": roof,
+        "roofline": head["roofline"],
+        "roofline_attention": head["roofline_attention"],
+        "roofline_row_stats": head["roofline_row_stats"],
+        "roofline_attn_accept": head["roofline_attn_accept"],
+        "other_workloads": others,
     }
     if not args.no_cpu_baseline:
+        print("[bench] CPU checker baseline", file=sys.stderr, flush=True)
         out["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(out))
     return 0

@@ -87,8 +87,11 @@ int cascade_destroy(cascade_ctx* ctx);
 const char* cascade_strerror(int status);
 /* Synchronises the ctx stream, returns CASCADE_OK or CASCADE_ETREE if any kernel since the last
  * call met a violated precondition (parent[i] >= i, more than CASCADE_MAX_WIDTH children, token
- * outside [0, vocab), tree deeper than max_depth, a kv_commit row without room or with a path entry
- * outside its tree), and clears the flag. */
+ * outside [0, vocab), tree deeper than max_depth, a tree with more nodes than the bound its launch was
+ * sized for - tree_attn_args.max_nodes_per_tree, cascade_limits.max_nodes_per_tree - whose nodes are
+ * then not verified: attention rows of such a tree are written as zeros with lse = -inf, acceptance
+ * scalars beyond the bound as zeros, the walk sees only the nodes inside the bound; a kv_commit row
+ * without room or with a path entry outside its tree), and clears the flag. */
 int cascade_device_status(cascade_ctx* ctx);
 /* Bytes of device workspace the ctx holds (HOST query). */
 int64_t cascade_workspace_bytes(const cascade_ctx* ctx);

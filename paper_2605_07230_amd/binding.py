@@ -297,7 +297,8 @@ def convergence_weights(ctx: Context, *, features, tau_seq: float, c: float, wei
 class DeviceStep:
     """Uploads a workloads.VerifyInputs record and owns the output buffers of one step."""
 
-    def __init__(self, inp, device="cuda:0", stream: Optional[torch.cuda.Stream] = None):
+    def __init__(self, inp, device="cuda:0", stream: Optional[torch.cuda.Stream] = None, max_tree: Optional[int] = None):
+        """max_tree overrides the bound on nodes per tree handed to the library (default: the largest tree)."""
         self.inp = inp
         dev = torch.device(device)
         dt = torch.bfloat16 if inp.dtype == "bf16" else torch.float32
@@ -317,7 +318,7 @@ class DeviceStep:
         self.draft_prob, self.u, self.u_bonus = up(inp.draft_prob), up(inp.u), up(inp.u_bonus)
         N_a, N_c, B = inp.q.shape[0], inp.n_nodes, inp.n_prompts
         self.max_depth = inp.max_depth
-        self.max_tree = int((inp.node_off[1:] - inp.node_off[:-1]).max())
+        self.max_tree = int((inp.node_off[1:] - inp.node_off[:-1]).max()) if max_tree is None else int(max_tree)
         f32, i32 = torch.float32, torch.int32
         self.attn_out = torch.empty((N_a, inp.n_heads, inp.head_dim), dtype=dt, device=dev)
         self.attn_lse = torch.empty((N_a, inp.n_heads), dtype=f32, device=dev)

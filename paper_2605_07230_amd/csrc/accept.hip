@@ -137,6 +137,14 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.y, node = blockIdx.x;
   const int lo = a.node_off[b], Tn = a.node_off[b + 1] - lo;
+  if (node == 0 && Tn > (int)gridDim.x) {
+    // the launch was sized for smaller trees: the nodes beyond it are flagged and written as zeros
+    if (tid == 0) atomicOr(dev_status, CASCADE_FLAG_TREE_SIZE);
+    for (int j = (int)gridDim.x + tid; j < Tn && lo + j < a.n_nodes_total; j += 256) {
+      a.q_tok[lo + j] = 0.f; a.m_int[lo + j] = 0.f; a.cos_parent[lo + j] = 0.f; a.n_int[lo + j] = 0;
+      a.m_conv[lo + j] = 0.f; a.n_conv[lo + j] = 0;
+    }
+  }
   if (node >= Tn) return;
   const int64_t gi = lo + node;
   // wave 0 scans the tree for siblings and children; its first chunk (parents and tokens of nodes

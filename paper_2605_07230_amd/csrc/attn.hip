@@ -38,6 +38,7 @@ struct AttnParams {
   int n_heads, n_kv_heads, group;
   int n_split, n_sb;
   int n_rows_total;  // N * Hq
+  int max_tree;      // the host's bound on any row's node count (the grid was sized for it)
   float scale_log2e;
 };
 
@@ -149,6 +150,31 @@ __device__ __forceinline__ unsigned xcd_local_order(unsigned h, unsigned nx, uns
 }
 
 
+// A row whose tree has more nodes than the host's bound is not computed (the grid and the LDS arrays
+// were sized for the bound): the precondition flag is raised and the row's outputs are still defined -
+// zeros and lse = -inf, or empty split partials that the merge kernel turns into the same.  Called by
+// every workgroup of such a row; the one with query block 0 of each (kv head, split) does the writing.
+template <int D, bool SPLIT>
+__device__ __forceinline__ void skip_oversize_row(const AttnParams& p, int lo, int T, int kvh, int sb, int split, int tid, int nthreads) {
+  if (sb != 0) return;
+  if (tid == 0) atomicOr(p.dev_status, CASCADE_FLAG_TREE_SIZE);
+  const int G = p.group;
+  const int Tc = min(T, p.n_rows_total / p.n_heads - lo);   // never past the packed arrays
+  for (int r = tid; r < Tc * G; r += nthreads) {
+    const int64_t rowg = (int64_t)(lo + r / G) * p.n_heads + kvh * G + r % G;
+    if (SPLIT) {
+      float* wm = p.ws_ml + ((int64_t)split * p.n_rows_total + rowg) * 2;
+      wm[0] = -INFINITY;
+      wm[1] = 0.f;
+    } else {
+      uint4* o = (uint4*)((uint16_t*)p.out + rowg * D);
+#pragma unroll
+      for (int c = 0; c < D / 8; ++c) o[c] = make_uint4(0, 0, 0, 0);
+      if (p.lse) p.lse[rowg] = -INFINITY;
+    }
+  }
+}
+
 // two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -208,6 +234,7 @@ __global__ __launch_bounds__(64 * NW, (NQ == 4 || NW == 8) ? 1 : 2) void attn_bf
   const int G = p.group;
   const int M = T * G;
   const int row0 = sb * RW;
+  if (T > p.max_tree) { skip_oversize_row<D, SPLIT>(p, lo, T, kvh, sb, split, tid, NT); return; }
   if (row0 >= M || T > CASCADE_MAX_TREE) return;
   const int n_pt = (P + KT - 1) / KT, n_tt = (T + KT - 1) / KT, nt = n_pt + n_tt;
   const int per = (nt + p.n_split - 1) / p.n_split;
@@ -497,6 +524,7 @@ __global__ __launch_bounds__(NKG * 256, (NKG == 1 ? 3 : 1)) void attn_bf16_kspli
   const int G = p.group;
   const int M = T * G;
   const int row0 = sb * 64;
+  if (T > p.max_tree) { skip_oversize_row<D, SPLIT>(p, lo, T, kvh, sb, split, tid, NT); return; }
   if (row0 >= M || T > CASCADE_MAX_TREE) return;
   const int n_pt = (P + KT - 1) / KT, n_tt = (T + KT - 1) / KT, nt = n_pt + n_tt;
   const int per = (nt + p.n_split - 1) / p.n_split;
@@ -777,6 +805,7 @@ __global__ __launch_bounds__(512) void attn_bf16_qsplit_kernel(AttnParams p) {
   const int G = p.group;
   const int M = T * G;
   const int row0 = sb * 16;
+  if (T > p.max_tree) { skip_oversize_row<D, false>(p, lo, T, kvh, sb, 0, tid, NT); return; }
   if (row0 >= M || T > 128) return;
   const int n_pt = (P + KT - 1) / KT, n_tt = (T + KT - 1) / KT, nt = n_pt + n_tt;
 
@@ -1015,7 +1044,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnParams p) {
     l += w * ml[1];
     o += w * *(const f32x4*)(p.ws_o + ((int64_t)c * p.n_rows_total + row) * D + 4 * d4);
   }
-  const float inv = 1.f / l;
+  const float inv = l > 0.f ? 1.f / l : 0.f;   // a skipped row (every partial empty) comes out as zeros, lse = -inf
   uint2 packed;
   packed.x = pack_bf16x2(o[0] * inv, o[1] * inv);
   packed.y = pack_bf16x2(o[2] * inv, o[3] * inv);
@@ -1047,6 +1076,7 @@ AttnParams make_params(cascade_ctx* ctx, const tree_attn_args* a) {
   p.n_split = 1;
   p.n_sb = 1;
   p.n_rows_total = a->n_nodes_total * a->n_heads;
+  p.max_tree = a->max_nodes_per_tree;
   const float scale = a->scale != 0.f ? a->scale : 1.f / sqrtf((float)a->head_dim);
   p.scale_log2e = scale * LOG2E;
   return p;

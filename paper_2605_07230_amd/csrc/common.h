@@ -55,7 +55,8 @@ enum {
   CASCADE_FLAG_TOKEN = 4,    // token outside [0, vocab)
   CASCADE_FLAG_DEPTH = 8,    // path longer than max_depth
   CASCADE_FLAG_CAPACITY = 16, // kv_commit: a row's cache has no room for root + accepted path
-  CASCADE_FLAG_PATH = 32     // kv_commit: a path entry outside the row's tree, or a bad row_prompt
+  CASCADE_FLAG_PATH = 32,    // kv_commit: a path entry outside the row's tree, or a bad row_prompt
+  CASCADE_FLAG_TREE_SIZE = 64  // a tree with more nodes than the bound the launch was sized for
 };
 
 // launchers (one translation unit each); all return hipError_t of the launch

@@ -56,6 +56,8 @@ __global__ __launch_bounds__(NT) void select_kernel(select_args a, int* dev_stat
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
   const int lo = a.node_off[b], Tn = min(a.node_off[b + 1] - lo, 64 * TCH);
+  // a tree larger than the launch was sized for is walked over its first 64 * TCH nodes only, and flagged
+  if (tid == 0 && a.node_off[b + 1] - lo > 64 * TCH) atomicOr(dev_status, CASCADE_FLAG_TREE_SIZE);
   const int maxd = min(a.max_depth, CASCADE_MAX_DEPTH);
   const float eps = a.eps_tvd;
 

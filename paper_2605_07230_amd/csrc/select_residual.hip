@@ -44,6 +44,7 @@ __global__ __launch_bounds__(1024) void select_residual_kernel(select_args a, in
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
   const int lo = a.node_off[b], Tn = min(a.node_off[b + 1] - lo, CASCADE_MAX_TREE);
+  if (tid == 0 && a.node_off[b + 1] - lo > CASCADE_MAX_TREE) atomicOr(dev_status, CASCADE_FLAG_TREE_SIZE);
   const int V = a.vocab;   // a multiple of 4, at most 16 * SEG (checked by the host)
   const int maxd = min(a.max_depth, CASCADE_MAX_DEPTH);
   const float eps = a.eps_tvd;

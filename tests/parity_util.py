@@ -54,6 +54,51 @@ def check_attention(inp, ds, rows=None, heads=None):
     return worst
 
 
+def check_attention_node_sample(inp, ds, n_picks=4, seed=0):
+    """EVERY (row, head) pair on a seeded sample of nodes.  A node's output depends only on the prefix
+    and its ancestors, so the checker is run on the root-to-node chain of each picked node as a chain
+    tree (the checker's own pins include that removing non-ancestors changes nothing); this compares
+    the picked nodes and all their ancestors."""
+    tol = TOL[inp.dtype]
+    rng = np.random.default_rng(seed)
+    got = ds.attn_out.float().cpu().numpy()
+    got_lse = ds.attn_lse.cpu().numpy()
+    group = inp.n_heads // inp.n_kv_heads
+    worst, n_cmp = 0.0, 0
+    for s in range(inp.n_rows):
+        lo, hi = int(inp.row_node_off[s]), int(inp.row_node_off[s + 1])
+        par = inp.row_parent[lo:hi]
+        kc_s, vc_s = inp.k_cache[[s]], inp.v_cache[[s]]
+        for g in range(inp.n_heads):
+            kv = g // group
+            picks = set(int(x) for x in rng.integers(0, hi - lo, size=n_picks)) | {hi - lo - 1}
+            for i in picks:
+                chain = np.asarray(vo.ancestors_or_self(par, i)) + lo
+                ref, ref_lse = vo.tree_attention(inp.q[chain][:, [g]], inp.k_tree[chain][:, [kv]], inp.v_tree[chain][:, [kv]],
+                                                 kc_s[:, [kv]], vc_s[:, [kv]], np.arange(-1, len(chain) - 1),
+                                                 np.array([0, len(chain)]), inp.prefix_len[[s]])
+                e = max_rel_err(got[chain, g], ref[:, 0])
+                el = max_rel_err(got_lse[chain, g], ref_lse[:, 0])
+                worst = max(worst, e, el)
+                n_cmp += len(chain)
+                assert e <= tol and el <= tol, f"attention row {s} head {g} chain of node {i}: {e:.3e} / lse {el:.3e} > {tol}"
+    return worst, n_cmp
+
+
+def check_logits_columns(inp, ds, n_cols=512, seed=0):
+    """Logits of ALL nodes on a seeded sample of vocabulary columns (the projection restricted to those
+    rows of W is the same definition; the row statistics need whole rows and are checked elsewhere)."""
+    tol = TOL[inp.dtype]
+    rng = np.random.default_rng(seed)
+    cols = np.sort(rng.choice(inp.vocab, size=min(n_cols, inp.vocab), replace=False))
+    g, _, _, _ = vo.lmhead_cfg(inp.h_cond, inp.h_uncond, inp.w[cols], inp.cfg_scale, inp.temperature, 0)
+    got = ds.logits[:, torch.from_numpy(cols).to(ds.logits.device)].cpu().numpy()
+    scale = np.abs(g).max(axis=1)                         # per node, as for whole rows
+    err = (np.abs(got - g).max(axis=1) / np.maximum(scale, 1e-30)).max()
+    assert err <= tol, f"logits column sample: max rel err {err:.3e} > {tol}"
+    return float(err)
+
+
 def check_lmhead(inp, ds, nodes=None):
     """Logits and row statistics against the checker (all nodes or a subset of them)."""
     tol = TOL[inp.dtype]

@@ -39,6 +39,25 @@ def test_chain_tree_equals_library_causal_attention():
     np.testing.assert_allclose(out, ref, rtol=1e-10, atol=1e-12)
 
 
+@pytest.mark.parametrize("scale", [None, 0.37])
+def test_chain_tree_lse_equals_library_logsumexp_of_scaled_causal_scores(scale):
+    # non-zero queries and a non-unit scale: a dropped maximum, a dropped scale or a wrong key set all show
+    T, P, Hq, Hkv, D = 7, 11, 4, 2, 8
+    parent = np.arange(-1, T - 1)
+    q, kt, vt, kc, vc, rp, off, plen = _rand_case(7, parent, P, Hq, Hkv, D)
+    q *= 3.0                                                                   # scores far from 0: max term matters
+    _, lse = vo.tree_attention(q, kt, vt, kc, vc, rp, off, plen, scale=scale)
+    sc = (1.0 / np.sqrt(D)) if scale is None else scale
+    from scipy.special import logsumexp
+    for g in range(Hq):
+        kv = g // (Hq // Hkv)
+        keys = np.concatenate([kc[0, kv, :P], kt[:, kv]], axis=0)              # [P+T, D]
+        scores = sc * (q[:, g] @ keys.T)                                       # [T, P+T]
+        for i in range(T):
+            want = logsumexp(scores[i, :P + i + 1])                            # causal: prefix + nodes 0..i
+            assert lse[i, g] == pytest.approx(want, rel=1e-12, abs=1e-12)
+
+
 def test_zero_query_reveals_attended_set():
     # q = 0 makes the softmax uniform, one-hot values then read off exactly which positions were attended
     parent = np.array([-1, 0, 0, 1, 1, 2, 5])
