@@ -163,6 +163,23 @@ typedef struct {
 } tree_attn_args;
 int tree_verify_attn(cascade_ctx* ctx, const tree_attn_args* args);
 
+/* tree_verify_attn_static — tree_verify_attn for callers that cannot allocate device memory and so
+ * cannot hold a cascade_ctx: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same results; the precondition flag and the
+ * split-KV partials live in a static device array of CASCADE_STATIC_SCRATCH_BYTES that every GPU
+ * the library runs on holds until the process ends.  The call allocates nothing and frees nothing.
+ *   hip_stream   the hipStream_t (as void*) the kernels are enqueued on; NULL = the default stream
+ *   status_out   DEVICE int32, nullable: receives 0, or the non-zero flag word if a tree precondition
+ *                was violated during this call (what cascade_device_status reports for a ctx)
+ * Limits: n_nodes_total * n_heads <= CASCADE_STATIC_MAX_QUERY_ROWS and head_dim <= 128, otherwise
+ * CASCADE_ESHAPE and nothing is enqueued (the other checks are tree_verify_attn's).  Within the
+ * limits the number of key splits is reduced to what fits the array.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race on it; calls on one stream, or otherwise ordered, are safe. */
+#define CASCADE_STATIC_MAX_QUERY_ROWS 32768
+#define CASCADE_STATIC_SCRATCH_BYTES (64u * 1024u * 1024u + 256u)
+int tree_verify_attn_static(void* hip_stream, const tree_attn_args* args, int32_t* status_out);
+
 /* ---------------------------------------------------------------------------------------------
  * lmhead_softmax_cfg — final projection at every tree node (Sec. 4.2: the O(hV) projection is
  * the dominant term), guidance mix, temperature, top-k and softmax statistics (App.

@@ -25,7 +25,7 @@ OK, EINVAL, ESHAPE, EDTYPE, ENOMEM, EHIP, ETREE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["cascade_create", "cascade_destroy", "cascade_strerror", "cascade_device_status", "cascade_workspace_bytes",
            "cascade_set_kernel_timing", "cascade_read_kernel_timing", "cascade_measure_hbm_read",
-           "cascade_measure_mfma_bf16", "cascade_pack_lmhead_w", "tree_verify_attn", "lmhead_softmax_cfg", "cascade_accept", "select_path", "kv_commit", "convergence_weights"]
+           "cascade_measure_mfma_bf16", "cascade_pack_lmhead_w", "tree_verify_attn", "tree_verify_attn_static", "lmhead_softmax_cfg", "cascade_accept", "select_path", "kv_commit", "convergence_weights"]
 
 _vp, _i32, _i64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
 
@@ -109,6 +109,8 @@ def load_library() -> C.CDLL:
     lib.cascade_measure_mfma_bf16.restype = C.c_int
     lib.cascade_pack_lmhead_w.argtypes = [_vp, _vp, _i32, _i32, _vp]
     lib.cascade_pack_lmhead_w.restype = C.c_int
+    lib.tree_verify_attn_static.argtypes = [_vp, C.POINTER(tree_attn_args), _vp]
+    lib.tree_verify_attn_static.restype = C.c_int
     for name, st in (("tree_verify_attn", tree_attn_args), ("lmhead_softmax_cfg", lmhead_args),
                      ("cascade_accept", accept_args), ("select_path", select_args), ("kv_commit", kv_commit_args),
                      ("convergence_weights", conv_weight_args)):
@@ -192,9 +194,8 @@ class Context:
         return out.value
 
 
-def tree_verify_attn(ctx: Context, *, node_off, parent, prefix_len, q, k_tree, v_tree, k_cache, v_cache, out,
-                     lse=None, scale: float = 0.0, max_nodes_per_tree: int, max_prefix_len: int) -> None:
-    """q/out [N,Hq,D], k_tree/v_tree [N,Hkv,D], k_cache/v_cache [S,Hkv,P_cap,D] (last dim contiguous)."""
+def _tree_attn_args(*, node_off, parent, prefix_len, q, k_tree, v_tree, k_cache, v_cache, out, lse, scale,
+                    max_nodes_per_tree, max_prefix_len) -> tree_attn_args:
     a = tree_attn_args()
     a.n_rows = prefix_len.numel()
     a.node_off, a.parent, a.prefix_len = _ptr(node_off), _ptr(parent), _ptr(prefix_len)
@@ -209,7 +210,28 @@ def tree_verify_attn(ctx: Context, *, node_off, parent, prefix_len, q, k_tree, v
         assert k_cache.stride() == v_cache.stride() and k_cache.stride(3) == 1
         a.cache_stride_row, a.cache_stride_head, a.cache_stride_pos = k_cache.stride(0), k_cache.stride(1), k_cache.stride(2)
     a.out, a.lse = _ptr(out), _ptr(lse)
+    return a
+
+
+def tree_verify_attn(ctx: Context, *, node_off, parent, prefix_len, q, k_tree, v_tree, k_cache, v_cache, out,
+                     lse=None, scale: float = 0.0, max_nodes_per_tree: int, max_prefix_len: int) -> None:
+    """q/out [N,Hq,D], k_tree/v_tree [N,Hkv,D], k_cache/v_cache [S,Hkv,P_cap,D] (last dim contiguous)."""
+    a = _tree_attn_args(node_off=node_off, parent=parent, prefix_len=prefix_len, q=q, k_tree=k_tree, v_tree=v_tree,
+                        k_cache=k_cache, v_cache=v_cache, out=out, lse=lse, scale=scale,
+                        max_nodes_per_tree=max_nodes_per_tree, max_prefix_len=max_prefix_len)
     _check(ctx.lib.tree_verify_attn(ctx.handle, C.byref(a)))
+
+
+def tree_verify_attn_static(stream: Optional[torch.cuda.Stream] = None, *, node_off, parent, prefix_len, q, k_tree, v_tree,
+                            k_cache, v_cache, out, lse=None, scale: float = 0.0, max_nodes_per_tree: int,
+                            max_prefix_len: int, status_out: Optional[torch.Tensor] = None) -> None:
+    """The same call without a context: scratch lives in the library's static device array, nothing is
+    allocated.  status_out: int32 device tensor of one element that receives the precondition flag word."""
+    a = _tree_attn_args(node_off=node_off, parent=parent, prefix_len=prefix_len, q=q, k_tree=k_tree, v_tree=v_tree,
+                        k_cache=k_cache, v_cache=v_cache, out=out, lse=lse, scale=scale,
+                        max_nodes_per_tree=max_nodes_per_tree, max_prefix_len=max_prefix_len)
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(load_library().tree_verify_attn_static(_vp(st.cuda_stream), C.byref(a), _ptr(status_out)))
 
 
 def cascade_pack_lmhead_w(ctx: Context, w: torch.Tensor) -> torch.Tensor:

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "common.h"
@@ -174,6 +175,88 @@ int tree_verify_attn(cascade_ctx* ctx, const tree_attn_args* a) {
   if (a->n_rows == 0 || a->n_nodes_total == 0) return CASCADE_OK;
   hipError_t e = (a->dtype == CASCADE_BF16) ? launch_tree_attn_bf16(ctx, a) : launch_tree_attn_f32(ctx, a);
   return e == hipSuccess ? CASCADE_OK : hip_fail(e);
+}
+
+// --------------------------------------------------------------------------------------------
+// tree_verify_attn_static: the same attention for callers that cannot allocate.  Everything the
+// kernels need beyond inputs and outputs (the precondition flag word and the split-KV partials)
+// lives in this file-scope device array instead of a context workspace.  Every GPU the library
+// runs on holds its own copy at its own address until the process ends; the name below is only a
+// host-side handle for hipGetSymbolAddress, never a pointer that may be handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[CASCADE_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_STATIC_DEVICES = 64;
+unsigned char* g_scratch_ptr[MAX_STATIC_DEVICES];   // device address of `scratch`, per device (null until first use)
+std::mutex g_scratch_mutex;
+
+// first word of the scratch array: cleared before the launch, copied out after it
+__global__ void static_status_kernel(int* flag, int* copy_to) {
+  if (copy_to) *copy_to = *flag;
+  else *flag = 0;
+}
+
+// device address of this device's copy of the array (looked up once per device, with that device current)
+int static_scratch(int device, unsigned char** out) {
+  if (device < 0 || device >= MAX_STATIC_DEVICES) return CASCADE_ESHAPE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!ptr) return CASCADE_EHIP;
+    g_scratch_ptr[device] = (unsigned char*)ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return CASCADE_OK;
+}
+
+}  // namespace
+
+int tree_verify_attn_static(void* hip_stream, const tree_attn_args* a, int32_t* status_out) {
+  if (!a) return CASCADE_EINVAL;
+  if (a->n_rows < 0 || a->n_nodes_total < 0 || a->n_heads <= 0 || a->head_dim <= 0 || a->max_nodes_per_tree < 0 || a->max_prefix_len < 0)
+    return CASCADE_EINVAL;
+  // the stated maximum: beyond it not even two splits' partials fit the array
+  if ((int64_t)a->n_nodes_total * a->n_heads > CASCADE_STATIC_MAX_QUERY_ROWS || a->head_dim > 128 ||
+      a->max_nodes_per_tree > CASCADE_MAX_TREE)
+    return CASCADE_ESHAPE;
+  int device = -1;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return hip_fail(e);
+  unsigned char* base = nullptr;
+  int st = static_scratch(device, &base);
+  if (st != CASCADE_OK) return st;
+  // a context on the stack that points into the static array: no workspace of its own, no timing events
+  cascade_ctx local;
+  memset(&local, 0, sizeof(local));
+  local.stream = (hipStream_t)hip_stream;
+  local.device = device;
+  local.lim.max_rows = a->n_rows;
+  local.lim.max_nodes_total = a->n_nodes_total;
+  local.lim.max_nodes_per_tree = a->max_nodes_per_tree;
+  local.lim.max_prefix = a->max_prefix_len;
+  local.lim.n_heads = a->n_heads;
+  local.lim.head_dim = a->head_dim;
+  local.ws = (char*)base;
+  local.ws_bytes = CASCADE_STATIC_SCRATCH_BYTES;
+  local.dev_status = (int*)base;
+  local.attn_ws = (char*)base + 256;
+  local.attn_ws_bytes = CASCADE_STATIC_SCRATCH_BYTES - 256;
+  // the flag word keeps the previous call's value: cleared by a one-thread kernel (not a memset node, so
+  // that a caller may capture the call into a graph)
+  hipLaunchKernelGGL(static_status_kernel, dim3(1), dim3(1), 0, local.stream, local.dev_status, (int*)nullptr);
+  e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  st = tree_verify_attn(&local, a);   // same validation, same dispatch, same kernels
+  if (st != CASCADE_OK) return st;
+  if (status_out) {
+    hipLaunchKernelGGL(static_status_kernel, dim3(1), dim3(1), 0, local.stream, local.dev_status, (int*)status_out);
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return CASCADE_OK;
 }
 
 int lmhead_softmax_cfg(cascade_ctx* ctx, const lmhead_args* a) {
