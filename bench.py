@@ -268,7 +268,8 @@ def measure_workload(index: int, steps: int, warmup: int, args, hbm_meas: float,
     if inp.dtype == "f32":
         attn_kernel = "attn_f32_kernel"
     elif m_rows > 128:
-        attn_kernel = "attn_bf16_kernel"
+        # 256 query rows per workgroup; the ring kernel unless the keys are split to fill an idle GPU
+        attn_kernel = "attn_bf16_kernel" if "attn_merge" in kernel_us else "attn_bf16_ring_kernel"
     else:
         attn_kernel = "attn_bf16_qsplit_kernel" if units <= 128 else "attn_bf16_ksplit_kernel"
     attn_us = kernel_us.get("attn", 0.0) + kernel_us.get("attn_merge", 0.0)

@@ -3,16 +3,22 @@
 // Every node of a row attends the row's prefix KV positions plus its ancestors in the drafted
 // tree plus itself (Preliminaries: parallel target pass; tree decoding with a tree mask).
 //
-// bf16 path: one workgroup = (row, kv head, query super-block, kv split).  K tiles (64 keys) are
-// staged row-major in LDS, V tiles transposed ([d][key]) so that both MFMA operands are read as
-// contiguous 8/16-byte LDS words.  Scores are produced TRANSPOSED, S^T = K Q^T, with
-// v_mfma_f32_16x16x32_bf16: a lane then owns one query column, so the online-softmax statistics
-// are per-lane scalars and the probabilities are already laid out as the B operand of
-// O^T = V^T P^T.  The ancestor mask of the 64 tree keys of a tile is one 64-bit word per query,
-// built in LDS by climbing parent pointers.  Split-KV partials go through the workspace and a
-// small merge kernel; with one split the kernel writes the final output.
+// bf16 path: one workgroup = (row, kv head, query super-block, kv split).  K and V tiles (64 keys) are
+// both staged row-major ([key][d]) in LDS; the K operand of the score MFMA is read as 16-byte words, the
+// V operand of the second MFMA through the transposing LDS read (ds_read_b64_tr_b16), so no tile is ever
+// transposed in memory.  Scores are produced TRANSPOSED, S^T = K Q^T, with v_mfma_f32_16x16x32_bf16: a
+// lane then owns one query column, so the online-softmax statistics are per-lane scalars and the
+// probabilities are already laid out as the B operand of O^T = V^T P^T.  The ancestor mask of the 64
+// tree keys of a tile is one 64-bit word per query, built in LDS by climbing parent pointers.  Four
+// kernels share this scheme and differ in how work is cut: query rows split over waves (tiny batches),
+// key groups inside the workgroup (small trees), 256 query rows per workgroup on a three-deep LDS ring
+// filled by LDS-direct loads (large trees), and the double-buffered predecessor of the latter, which
+// writes split-KV partials to the workspace for a small merge kernel when the keys must be split across
+// workgroups to fill the GPU.
 //
 // f32 path: a plain one-workgroup-per-(node, head) kernel, used by the small fp32 configuration.
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -473,6 +479,397 @@ __global__ __launch_bounds__(64 * NW, (NQ == 4 || NW == 8) ? 1 : 2) void attn_bf
       }
       if (g == 0 && p.lse) p.lse[out_row[n]] = m_run[n] * LN2 + logf(l);
     }
+  }
+}
+
+// A wave's own LDS-direct loads have landed when at most the N youngest are outstanding; its LDS writes and
+// reads are complete at lgkmcnt(0); then the workgroup barrier, bare (a fenced barrier would wait for every
+// outstanding load, i.e. for the whole prefetch ring).
+template <int N>
+__device__ __forceinline__ void wait_and_sync() {
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// ---------------------------------------------------------------------- bf16, large trees
+// Workgroup = (row, kv head, 256 query rows, kv split): eight waves x two 16-row query blocks share every
+// 64-key K / V tile.  Tiles never pass through registers on their way in: 16-byte LDS-direct loads
+// (global_load_lds_dwordx4, M0 = LDS address of the wave's 1 KiB chunk) write them into two rings of NS
+// tiles each, NS - 1 tiles ahead of their use; a wave waits only for its own chunks of the tile that is
+// needed next (vmcnt), then one bare s_barrier per tile makes everybody's chunks visible and the oldest
+// tile's buffer free.  An LDS-direct load puts lane l's 16 bytes at 16 l behind M0, so a tile cannot be
+// padded; bank conflicts are avoided by choosing WHICH 16-byte piece of a key row each lane fetches: LDS
+// slot q of row r holds piece q ^ swz(r) (K: the 16 keys a score MFMA reads together land in 16 different
+// slots; V: the 8 keys x 32 bytes of half a transposing read likewise).
+// The loop is software-pipelined inside a wave: the score MFMAs of tile t+1 are issued between the
+// exponentials of tile t (matrix cores and vector ALU run side by side), then the PV MFMAs of tile t.
+// The running maximum that the exponentials refer to is only moved when a row's maximum has grown by
+// more than 2^8 (the result does not depend on the reference, p <= 256 is exact enough in bf16 and far
+// from overflow in the float accumulators), so the accumulator rescale is a rarely taken branch.
+template <int D>
+struct RingGeom {
+  static constexpr int RB = 2 * D;        // bytes per key row
+  static constexpr int PPR = RB / 16;     // 16-byte pieces per row
+  static constexpr int RPC = 1024 / RB;   // rows per 1 KiB chunk (one wave-wide LDS-direct load)
+  static constexpr int CPT = KT / RPC;    // chunks per tile
+  static constexpr int TILE = KT * RB;    // bytes per K (or V) tile
+  // slot swizzles (see above); both depend on the key index modulo 16 only
+  __device__ static constexpr int kswz(int key) { return D == 128 ? (key & 15) : ((key >> 1) & 7); }
+  __device__ static constexpr int vswz(int key) { return D == 128 ? 2 * (key & 7) : 2 * ((key >> 1) & 3); }
+};
+
+constexpr float RESCALE_STEP = 8.f;   // log2 units
+
+// Maxima of MFMA results (or -inf).  The IEEE-754-2019 maximum maps to v_maximum3_f32 without the input-quieting
+// copies that fmaxf costs in IEEE mode.  It must stay a compiler-visible operation: a vector ALU instruction that
+// reads a register too soon after the matrix core was told to write it gets the register's OLD contents, the
+// hardware does not interlock that case, and the compiler pads only the instructions it can see - the same
+// maximum written as inline assembly read stale registers whenever the scheduler put it right behind its MFMA.
+__device__ __forceinline__ float vmax3(float a, float b, float c) {
+  return __builtin_elementwise_maximum(__builtin_elementwise_maximum(a, b), c);
+}
+__device__ __forceinline__ float vmax2(float a, float b) { return __builtin_elementwise_maximum(a, b); }
+__device__ __forceinline__ float rows4_max_raw(float v) {
+  cascade_u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = vmax2(__uint_as_float(a.x), __uint_as_float(a.y));
+  cascade_u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return vmax2(__uint_as_float(b.x), __uint_as_float(b.y));
+}
+
+template <int D, int NS>
+__global__ __launch_bounds__(512, 1) void attn_bf16_ring_kernel(AttnParams p) {
+  using GM = RingGeom<D>;
+  constexpr int NW = 8, NQ = 2, NT = 64 * NW, RW = 16 * NQ * NW;
+  constexpr int KS = D / 32, DB = D / 16;
+  constexpr int CPW = GM::CPT / NW;     // chunks of K (and of V) a wave loads per tile: 2 (D = 128) or 1 (D = 64)
+  constexpr int LPI = 2 * CPW;          // LDS-direct loads a wave issues per iteration
+  static_assert(GM::CPT % NW == 0 && NS == 3, "ring geometry: the loop below is unrolled three times");
+  extern __shared__ __align__(1024) char ring_smem[];
+  char* const smem_raw = ring_smem;
+  // [K ring: NS tiles][V ring: NS tiles][parent: CASCADE_MAX_TREE ints][ancestor words: 2 x RW]
+  int* s_parent = (int*)(smem_raw + 2 * NS * GM::TILE);
+  unsigned long long* s_anc = (unsigned long long*)(s_parent + CASCADE_MAX_TREE);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, g = lane >> 4;
+  const unsigned nx = gridDim.x, ny = gridDim.y;
+  const unsigned lid = xcd_local_order(blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z), nx, ny * gridDim.z);
+  const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny);
+  const int s = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, lane);
+  const int sb = bx;   // the keys of a row are never split across workgroups here (n_split == 1)
+  const int lo = p.node_off[s];
+  const int T = p.node_off[s + 1] - lo;
+  const int P = p.prefix_len[s];
+  const int G = p.group;
+  const int M = T * G;
+  const int row0 = sb * RW;
+  if (T > p.max_tree) { skip_oversize_row<D, false>(p, lo, T, kvh, sb, 0, tid, NT); return; }
+  if (row0 >= M || T > CASCADE_MAX_TREE) return;
+  const int n_pt = (P + KT - 1) / KT, n_tt = (T + KT - 1) / KT, nt = n_pt + n_tt;
+  const int t_begin = 0, t_end = nt;   // nt >= 1: a tree has at least its root
+
+  const char* kc = (const char*)((const uint16_t*)p.k_cache + s * p.sr + kvh * p.sh);
+  const char* vc = (const char*)((const uint16_t*)p.v_cache + s * p.sr + kvh * p.sh);
+  const char* ktr = (const char*)((const uint16_t*)p.k_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D);
+  const char* vtr = (const char*)((const uint16_t*)p.v_tree + ((int64_t)lo * p.n_kv_heads + kvh) * D);
+  const unsigned tree_pitch_b = (unsigned)(p.n_kv_heads * D * 2), cache_pitch_b = (unsigned)(p.sp * 2);
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)smem_raw);
+
+  // ---- loader: chunk c = CPW wave + i of a tile; lane -> row c RPC + lane / PPR, LDS slot lane % PPR.
+  // Ring stages are numbered by the workgroup's own tile count (tile t lives in stage (t - t_begin) % NS), so
+  // that inside the loop, which is unrolled NS times, every LDS address is a per-lane register + a constant.
+  int ld_row[CPW];
+  unsigned ld_kpiece[CPW], ld_vpiece[CPW], ld_kfull[CPW], ld_vfull[CPW];
+#pragma unroll
+  for (int i = 0; i < CPW; ++i) {
+    const int r = (CPW * wave + i) * GM::RPC + lane / GM::PPR, q = lane % GM::PPR;
+    ld_row[i] = r;
+    ld_kpiece[i] = 16u * (unsigned)(q ^ GM::kswz(r));
+    ld_vpiece[i] = 16u * (unsigned)(q ^ GM::vswz(r));
+    ld_kfull[i] = (unsigned)r * cache_pitch_b + ld_kpiece[i];   // offsets inside a whole prefix tile
+    ld_vfull[i] = (unsigned)r * cache_pitch_b + ld_vpiece[i];
+  }
+  // One matrix (K or V) of tile tk into ring stage `stage`.  tk is clamped to the workgroup's last tile (the
+  // extra requests keep the per-iteration load count fixed; their data lands in a free stage and is never
+  // used); rows past the end of the tile's source are read from its last row (always in bounds; their scores
+  // are masked, so the finite clamped values contribute exactly nothing).
+  auto request = [&](int tk, int stage, bool is_v) {
+    const int tc = min(tk, t_end - 1);
+    const unsigned ldst = lds0 + (is_v ? NS * GM::TILE : 0) + stage * GM::TILE + CPW * wave * 1024;
+    if (tc < n_pt && (tc + 1) * KT <= P) {
+      // a whole tile of the prefix: nothing to clamp, the per-lane offsets are constants
+      const char* src = (is_v ? vc : kc) + (int64_t)tc * KT * cache_pitch_b;
+#pragma unroll
+      for (int i = 0; i < CPW; ++i) {
+        const unsigned l = ldst + i * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(is_v ? ld_vfull[i] : ld_kfull[i]), "s"(src) : "memory");
+      }
+    } else {
+      const bool tree_tile = tc >= n_pt;
+      const int kb = tree_tile ? (tc - n_pt) * KT : tc * KT;
+      const int lim = (tree_tile ? T : P) - 1 - kb;                 // last valid row of the tile, >= 0
+      const unsigned pitch_b = tree_tile ? tree_pitch_b : cache_pitch_b;
+      const char* src = (is_v ? (tree_tile ? vtr : vc) : (tree_tile ? ktr : kc)) + (int64_t)kb * pitch_b;
+#pragma unroll
+      for (int i = 0; i < CPW; ++i) {
+        const unsigned voff = (unsigned)min(ld_row[i], lim) * pitch_b + (is_v ? ld_vpiece[i] : ld_kpiece[i]);
+        const unsigned l = ldst + i * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(voff), "s"(src) : "memory");
+      }
+    }
+  };
+
+  // ancestor-or-self words of tree tile tt (tile index in the workgroup's numbering) for the 256 query rows
+  auto build_mask = [&](int tt) {
+    if (tid < RW) {
+      const int kbase = (tt - n_pt) * KT;
+      const int r = row0 + tid;
+      unsigned long long wbits = 0ull;
+      if (r < M) {
+        int a = r % T, guard = 0;
+        while (a >= 0 && guard++ <= CASCADE_MAX_TREE) {
+          const int rel = a - kbase;
+          if (rel < 0) break;   // ancestors only get smaller
+          if (rel < 64) wbits |= 1ull << rel;
+          a = s_parent[a];
+        }
+      }
+      s_anc[(tt & 1) * RW + tid] = wbits;
+    }
+  };
+
+  // ---- prologue: K(t_begin) first, then the steady-state order K(t + NS), V(t + NS - 1) of iterations -NS+1 .. -1
+  request(t_begin, 0, false);
+#pragma unroll
+  for (int i = 1 - NS; i < 0; ++i) {
+    request(t_begin + i + NS, (i + NS) % NS, false);
+    request(t_begin + i + NS - 1, (i + NS - 1) % NS, true);
+  }
+  if (t_end > n_pt) {
+    for (int i = tid; i < T; i += NT) {
+      int pi = p.parent[lo + i];
+      if (pi >= i || pi < -1 || (i == 0 && pi != -1) || (i > 0 && pi < 0)) {
+        atomicOr(p.dev_status, CASCADE_FLAG_PARENT);
+        pi = (i == 0) ? -1 : 0;   // keep the climb finite
+      }
+      s_parent[i] = pi;
+    }
+  }
+  // query fragments (B operand of S^T): lane = (query l16, d group g)
+  Frag8 qf[NQ][KS];
+  int64_t out_row[NQ];   // index into [N*Hq] or -1
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    const int r = row0 + 16 * (wave + NW * n) + l16;
+    const bool ok = r < M;
+    const int i = ok ? r % T : 0, hg = ok ? r / T : 0;
+    const int64_t rowg = (int64_t)(lo + i) * p.n_heads + kvh * G + hg;
+    out_row[n] = ok ? rowg : -1;
+    const uint16_t* qp = (const uint16_t*)p.q + rowg * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ok) qf[n][ks].u = *(const uint4*)(qp + 32 * ks);
+      else qf[n][ks].u = make_uint4(0, 0, 0, 0);
+    }
+  }
+  f32x4 ot[NQ][DB];
+  f32x4 lsum[NQ];        // row sums of the (bf16) probabilities, produced by the matrix cores: every entry holds the sum
+  float m_ref[NQ];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    m_ref[n] = -INFINITY;
+    lsum[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int db = 0; db < DB; ++db) ot[n][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  Frag8 ones;            // a V^T fragment of bf16 ones: ones x P^T = the probabilities' row sums
+  ones.u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+
+  // ---- LDS read addresses.  K fragment (kt, ks): key 16 kt + l16, pieces of d 32 ks + 8 g: slot (4 ks + g) ^ swz;
+  // V operand (db, j): keys 32 j + 4 g + (l16 >> 2) (+ 16), 4 consecutive d at 16 db + 4 (l16 & 3): slot
+  // (2 db + ((l16 & 3) >> 1)) ^ swz.  ks and db enter by XOR into a per-lane constant (one register each), the
+  // stage, kt and j are compile-time byte offsets.
+  const unsigned k_lane = (unsigned)(l16 * GM::RB) + 16u * (unsigned)(g ^ GM::kswz(l16));
+  const int vkey = 4 * g + (l16 >> 2);
+  const unsigned v_lane = (unsigned)(vkey * GM::RB) + ((16u * (unsigned)((l16 & 3) >> 1)) ^ (16u * (unsigned)GM::vswz(vkey))) + 8u * (unsigned)(l16 & 1);
+  static_assert(GM::kswz(0) == GM::kswz(16) && GM::vswz(3) == GM::vswz(19) && GM::vswz(3) == GM::vswz(35), "swizzles have period 16");
+  const char* k_addr[KS];
+  const char* v_addr[DB];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_addr[ks] = smem_raw + (k_lane ^ (unsigned)(64 * ks));
+#pragma unroll
+  for (int db = 0; db < DB; ++db) v_addr[db] = smem_raw + NS * GM::TILE + (v_lane ^ (unsigned)(32 * db));
+
+  f32x4 st[NQ][4];   // scores: st[n][kt] holds keys 16 kt + 4 g + c for query l16
+  // K fragments of one 16-key sub-tile kt of the tile in K stage `stage` (A operand of S^T = K Q^T)
+  auto load_kfrags = [&](Frag8 (&kf)[KS], int stage, int kt) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kf[ks].u = *(const uint4*)(k_addr[ks] + stage * GM::TILE + 16 * kt * GM::RB);
+  };
+  auto score_kt = [&](const Frag8 (&kf)[KS], int kt) {
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) st[n][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) st[n][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks].v, qf[n][ks].v, st[n][kt], 0, 0, 0);
+  };
+  // V operand of step i = (db, j) = (i / 2, i % 2) of the tile in V stage `stage`: keys 32 j + 4 g + {0..3} and
+  // 32 j + 16 + 4 g + {0..3} at d = 16 db + l16, fetched by two transposing loads from the row-major tile
+  union VFrag { Frag8 f; s16x4 h[2]; };
+  auto load_vfrag = [&](VFrag& vf, int stage, int i) {
+    const char* vp = v_addr[i >> 1] + stage * GM::TILE + 32 * (i & 1) * GM::RB;
+    vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp));
+    vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(vp + 16 * GM::RB));
+  };
+  // largest of a lane's 16 scores of query block n (raw, before the scale)
+  auto lane_max = [&](int n) {
+    float a = vmax3(st[n][0][0], st[n][0][1], st[n][0][2]);
+    a = vmax3(a, st[n][0][3], st[n][1][0]);
+    a = vmax3(a, st[n][1][1], st[n][1][2]);
+    a = vmax3(a, st[n][1][3], st[n][2][0]);
+    a = vmax3(a, st[n][2][1], st[n][2][2]);
+    a = vmax3(a, st[n][2][3], st[n][3][0]);
+    a = vmax3(a, st[n][3][1], st[n][3][2]);
+    return vmax2(a, st[n][3][3]);
+  };
+
+  __syncthreads();                    // parent array complete (the compiler's own waits cover its loads)
+  if (t_begin >= n_pt) build_mask(t_begin);
+  wait_and_sync<LPI * (NS - 1)>();    // K(t_begin) everywhere (and the first mask)
+  float lmax[NQ];                     // lane_max of the scores in st (valid for tiles that need no mask)
+  {
+    Frag8 kf[2][KS];
+    load_kfrags(kf[0], 0, 0);
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      if (kt < 3) load_kfrags(kf[(kt + 1) & 1], 0, kt + 1);
+      score_kt(kf[kt & 1], kt);
+    }
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) lmax[n] = lane_max(n);
+  }
+
+  // One tile.  ST = ring stage of tile t (compile time: the loop below is unrolled NS times).
+  auto tile_step = [&](int t, auto st_const) {
+    constexpr int ST = decltype(st_const)::value;
+    constexpr int ST_K = (ST + 1) % NS;             // stage of K(t+1)
+    constexpr int ST_VNEW = (ST + NS - 1) % NS;     // stage V(t + NS - 1) goes to (V(t-1) has been consumed)
+    const bool tree_tile = t >= n_pt;
+    const int kbase = tree_tile ? (t - n_pt) * KT : t * KT;
+    const int rem = (tree_tile ? T : P) - kbase;
+    wait_and_sync<LPI * (NS - 2)>();   // K(t+1), V(t) landed everywhere; K(t), V(t-1) free
+    request(t + NS, ST, false);
+    request(t + NS - 1, ST_VNEW, true);
+    Frag8 kf[2][KS];
+    load_kfrags(kf[0], ST_K, 0);       // in flight during the reference check
+    if (t + 1 < t_end && t + 1 >= n_pt) build_mask(t + 1);   // read after the next barrier
+
+    // ---- masks (tree tiles and the ragged last prefix tile) and the reference of the exponentials
+    if (tree_tile || rem < KT) {
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        unsigned long long valid = tree_tile ? s_anc[(t & 1) * RW + 16 * (wave + NW * n) + l16]
+                                             : (rem >= 64 ? ~0ull : ((1ull << rem) - 1ull));
+        if (out_row[n] < 0) valid = 0ull;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+          const uint32_t nib = (uint32_t)(valid >> (16 * kt + 4 * g));   // this lane's 4 keys of sub-tile kt
+#pragma unroll
+          for (int c = 0; c < 4; ++c) st[n][kt][c] = ((nib >> c) & 1u) ? st[n][kt][c] : -INFINITY;
+        }
+        lmax[n] = lane_max(n);
+      }
+    }
+    // a lane sees 16 of its row's 64 scores; if none of a wave's lanes exceeds its row's reference by more than
+    // the step, no row does, and the reference stays (scale > 0: the maximum commutes with it)
+    bool moved = false;
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) moved |= lmax[n] * p.scale_log2e > m_ref[n] + RESCALE_STEP;   // -inf + 8 = -inf: a first finite score always moves it
+    if (__ballot(moved) != 0ull) {
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        const float mx = rows4_max_raw(lmax[n]) * p.scale_log2e;
+        const float m_new = (mx > m_ref[n] + RESCALE_STEP) ? mx : m_ref[n];
+        const float use_new = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_ref[n] - use_new);   // -inf - finite = -inf -> 0 ; equal -> 1
+        lsum[n] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) ot[n][db] *= alpha;
+        m_ref[n] = m_new;
+      }
+    }
+    float m_neg[NQ];
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) m_neg[n] = (m_ref[n] == -INFINITY) ? 0.f : -m_ref[n];
+
+    // ---- probabilities of tile t and scores of tile t+1.  Sub-tile kt's scores are consumed by the exponentials
+    // (and packed as the B operand of the second MFMA) before the MFMAs of tile t+1 overwrite the same registers,
+    // so the matrix cores work on sub-tile kt while the vector ALU is busy with sub-tile kt + 1.
+    Frag8 pf[NQ][2];
+    auto probs_kt = [&](int kt) {
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        float e[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) e[c] = fast_exp2(fmaf(st[n][kt][c], p.scale_log2e, m_neg[n]));   // -inf stays -inf -> 0
+        const uint32_t lo2 = pack_bf16x2(e[0], e[1]), hi2 = pack_bf16x2(e[2], e[3]);
+        if (kt & 1) { pf[n][kt >> 1].u.z = lo2; pf[n][kt >> 1].u.w = hi2; }
+        else { pf[n][kt >> 1].u.x = lo2; pf[n][kt >> 1].u.y = hi2; }
+      }
+    };
+    constexpr int NVS = 2 * DB, VW = 4;   // V steps per tile, steps whose fragments are requested ahead
+    VFrag vf[VW];
+    probs_kt(0);
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      if (kt < 3) load_kfrags(kf[(kt + 1) & 1], ST_K, kt + 1);
+      else {
+#pragma unroll
+        for (int i = 0; i < VW; ++i) load_vfrag(vf[i], ST, i);
+      }
+      score_kt(kf[kt & 1], kt);
+      if (kt < 3) probs_kt(kt + 1);
+    }
+
+    // ---- O^T += V^T P^T, row sums += ones P^T; the vector ALU meanwhile looks at the next tile's scores
+#pragma unroll
+    for (int n = 0; n < NQ; ++n)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) lsum[n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones.v, pf[n][j].v, lsum[n], 0, 0, 0);
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) lmax[n] = lane_max(n);
+#pragma unroll
+    for (int i = 0; i < NVS; ++i) {
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) ot[n][i >> 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[i % VW].f.v, pf[n][i & 1].v, ot[n][i >> 1], 0, 0, 0);
+      if (i + VW < NVS) load_vfrag(vf[i % VW], ST, i + VW);
+    }
+  };
+
+  for (int t = t_begin; t < t_end; t += NS) {
+    tile_step(t, std::integral_constant<int, 0>{});
+    if (t + 1 >= t_end) break;
+    tile_step(t + 1, std::integral_constant<int, 1>{});
+    if (t + 2 >= t_end) break;
+    tile_step(t + 2, std::integral_constant<int, 2>{});
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the clamped extra requests must not outlive the workgroup's LDS
+
+  // epilogue: lane (query l16, g) owns d = 16*db + 4*g + c
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    const float l = lsum[n][0];
+    if (out_row[n] < 0) continue;
+    const float inv = 1.f / l;   // l >= 1: the node's own key is never masked
+    uint16_t* o = (uint16_t*)p.out + out_row[n] * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      uint2 w;
+      w.x = pack_bf16x2(ot[n][db][0] * inv, ot[n][db][1] * inv);
+      w.y = pack_bf16x2(ot[n][db][2] * inv, ot[n][db][3] * inv);
+      *(uint2*)(o + 16 * db + 4 * g) = w;
+    }
+    if (g == 0 && p.lse) p.lse[out_row[n]] = m_ref[n] * LN2 + logf(l);
   }
 }
 
@@ -1082,28 +1479,39 @@ AttnParams make_params(cascade_ctx* ctx, const tree_attn_args* a) {
   return p;
 }
 
+// whole rows of keys per workgroup (n_split == 1): the ring kernel
+template <int D>
+hipError_t launch_ring_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
+  constexpr int NS = 3;
+  const size_t smem = 2 * NS * RingGeom<D>::TILE + CASCADE_MAX_TREE * sizeof(int) + 2 * 256 * sizeof(unsigned long long);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_ring_kernel<D, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  KernelTimer t(ctx, CASCADE_K_ATTN);
+  CASCADE_TIMED_LAUNCH(t, (attn_bf16_ring_kernel<D, NS>), grid, dim3(512), smem, ctx->stream, p);
+  return hipGetLastError();
+}
+
+// keys split across workgroups (n_split > 1): partials, then the merge kernel
 template <int D, int NQ, int NW>
-hipError_t launch_bf16_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
+hipError_t launch_split_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
   hipStream_t st = ctx->stream;
   const size_t smem = 2 * sizeof(TileSmem<D>) + CASCADE_MAX_TREE * sizeof(int) + 2 * 256 * sizeof(unsigned long long);
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_kernel<D, NQ, NW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_bf16_kernel<D, NQ, NW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  if (p.n_split > 1) {
-    {
-      KernelTimer t(ctx, CASCADE_K_ATTN);
-      CASCADE_TIMED_LAUNCH(t, (attn_bf16_kernel<D, NQ, NW, true>), grid, dim3(64 * NW), smem, st, p);
-    }
-    KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
-    CASCADE_TIMED_LAUNCH(t, (attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
-  } else {
+  {
     KernelTimer t(ctx, CASCADE_K_ATTN);
-    CASCADE_TIMED_LAUNCH(t, (attn_bf16_kernel<D, NQ, NW, false>), grid, dim3(64 * NW), smem, st, p);
+    CASCADE_TIMED_LAUNCH(t, (attn_bf16_kernel<D, NQ, NW, true>), grid, dim3(64 * NW), smem, st, p);
   }
+  KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
+  CASCADE_TIMED_LAUNCH(t, (attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 
@@ -1215,5 +1623,9 @@ hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a) {
     p.ws_ml = (float*)(ctx->attn_ws + (size_t)n_split * p.n_rows_total * a->head_dim * sizeof(float));
   }
   dim3 grid(n_split * p.n_sb, a->n_kv_heads, a->n_rows);
-  return a->head_dim == 128 ? launch_bf16_t<128, 2, NW>(ctx, p, grid) : launch_bf16_t<64, 2, NW>(ctx, p, grid);
+  // Both kernels cover 256 query rows per workgroup.  With whole rows of keys per workgroup the ring kernel runs
+  // (tiles straight into LDS, three deep); when the keys are split to fill an otherwise idle GPU, the older
+  // double-buffered kernel writes the partials (the ring kernel's register budget has no room for that epilogue).
+  if (n_split > 1) return a->head_dim == 128 ? launch_split_t<128, 2, NW>(ctx, p, grid) : launch_split_t<64, 2, NW>(ctx, p, grid);
+  return a->head_dim == 128 ? launch_ring_t<128>(ctx, p, grid) : launch_ring_t<64>(ctx, p, grid);
 }

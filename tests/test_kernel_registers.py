@@ -48,3 +48,29 @@ def test_tiled_projection_m0_and_waits(tmp_path):
         loop = loop[:loop.index("s_cbranch_scc")]
         assert "vmcnt(0)" not in loop, name
         assert loop.count("s_barrier") == 4 and loop.count("v_mfma_f32_32x32x16_bf16") == 64
+
+
+def test_ring_attention_m0_and_waits(tmp_path):
+    """The large-tree attention kernel fills its LDS rings with LDS-direct loads (M0 set by hand) three
+    tiles ahead and waits with partial counts: inside the tile loop (unrolled once per ring stage, one
+    barrier each) there must be no wait for ALL outstanding loads, and nothing in the kernel may go
+    through scratch memory; the only full wait is the one that drains the ring before the epilogue."""
+    _, text = _kernel_stats("attn.hip", tmp_path)
+    bodies = re.findall(r"^(_ZN\S*attn_bf16_ring_kernel\S*):[^\n]*\n(.*?)s_endpgm", text, flags=re.S | re.M)
+    assert len(bodies) == 2
+    for name, body in bodies:
+        m0 = [l.strip() for l in body.splitlines() if re.search(r"\bm0\b", l)]
+        assert m0 and all(l.startswith("s_mov_b32 m0,") for l in m0), (name, m0[:5])
+        assert "scratch_" not in body, name
+        start = body.index("=>This Loop Header: Depth=1")       # the tile loop (it has the masks' climbs inside)
+        end = body.rindex("vmcnt(0)")                           # the drain after the loop
+        loop = body[start:end]
+        assert "vmcnt(0)" not in loop, name
+        assert loop.count("s_barrier") == 3, name
+        assert loop.count("global_load_lds_dwordx4") >= 6
+        # Inline assembly is invisible to the compiler's hazard padding: a vector ALU instruction in it could read
+        # an MFMA result before the matrix core has written it.  Only waits, barriers, M0 and the LDS-direct
+        # loads may be written that way.
+        inline = re.findall(r";;#ASMSTART\n(.*?);;#ASMEND", body, flags=re.S)
+        ops = {l.split()[0] for blk in inline for l in blk.strip().splitlines()}
+        assert ops <= {"s_waitcnt", "s_barrier", "s_mov_b32", "s_nop", "global_load_lds_dwordx4"}, (name, ops)
