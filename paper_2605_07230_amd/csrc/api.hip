@@ -56,6 +56,8 @@ int cascade_create(cascade_ctx** out, const cascade_limits* lim, void* hip_strea
   c->lim = *lim;
   hipError_t e = hipGetDevice(&c->device);
   if (e != hipSuccess) { delete c; return hip_fail(e); }
+  e = hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device);
+  if (e != hipSuccess || c->n_cu <= 0) { delete c; return hip_fail(e != hipSuccess ? e : hipErrorInvalidDevice); }
   // split-KV partials: up to 16 splits, capped at 256 MiB (fewer splits are used if it does not fit)
   const size_t per_split = (size_t)lim->max_nodes_total * lim->n_heads * (lim->head_dim + 2) * sizeof(float);
   size_t attn = per_split * 16;

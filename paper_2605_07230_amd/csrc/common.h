@@ -13,6 +13,7 @@ struct cascade_ctx {
   hipStream_t stream;
   cascade_limits lim;
   int device;
+  int n_cu;               // compute units of the device (persistent kernels size their grids by it)
   char* ws;               // device workspace
   size_t ws_bytes;
   int* dev_status;        // one int at the start of ws: sticky precondition flag

@@ -481,11 +481,15 @@ __device__ __forceinline__ float key_f32(uint32_t k) {
 // (A row whose entries all share one bin, e.g. all equal, serialises on one LDS address: slow, exact.)
 template <int BPT>   // bins per thread; the workgroup's 1024 threads cover 1024 * BPT bins, highest first
 __device__ __forceinline__ void find_bin_from_top(const int* hist, int k, int tid, int lane, int wave, int* s_wsum, int* s_bin,
-                                                  int* s_above) {
+                                                  int* s_above, int pad_bin, int pad) {   // pad entries of bin pad_bin are not part of the row
   constexpr int NB = 1024 * BPT;
   int hb[BPT], loc = 0;
 #pragma unroll
-  for (int i = 0; i < BPT; ++i) { hb[i] = hist[NB - 1 - (BPT * tid + i)]; loc += hb[i]; }
+  for (int i = 0; i < BPT; ++i) {
+    const int b = NB - 1 - (BPT * tid + i);
+    hb[i] = hist[b] - (b == pad_bin ? pad : 0);
+    loc += hb[i];
+  }
   const int incl = wave_scan_incl_i(loc);
   if (lane == 63) s_wsum[wave] = incl;
   __syncthreads();
@@ -499,83 +503,220 @@ __device__ __forceinline__ void find_bin_from_top(const int* hist, int k, int ti
   __syncthreads();
 }
 
-template <int VPT>
-__global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
-  __shared__ float fred[16];
-  __shared__ int hist1[4096], hist2[1024], hist3[1024];
-  __shared__ int s_wsum[16];
-  __shared__ int s_bin, s_above;
-  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int V = p.vocab;
-  const float* g = p.logits + (int64_t)row * V;
-  const bool topk = p.top_k > 0 && p.top_k < V;
-  // the row is held as order-preserving integer keys; values are recovered from them when needed
-  uint32_t key[VPT];
-  float mx = -INFINITY;
-#pragma unroll
-  for (int i = 0; i < VPT; ++i) {
-    const int v = tid + 1024 * i;
-    const float xv = v < V ? g[v] : -INFINITY;
-    key[i] = f32_key(xv);
-    mx = fmaxf(mx, xv);
-  }
-  if (topk) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) hist1[tid + 1024 * i] = 0;
-    hist2[tid] = 0;
-    hist3[tid] = 0;
-  }
-  mx = wave_max(mx);
-  if (lane == 0) fred[wave] = mx;
-  __syncthreads();
-  mx = fred[0];
-#pragma unroll
-  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, fred[w]);
+// Row statistics.  One workgroup of 1024 threads per row; the row lives in registers (VPT values per thread,
+// loaded 16 bytes at a time when the row allows it).
+//
+// Fast path (top-k active): the order-preserving radix rounds above put sign, exponent and three mantissa bits
+// into the first digit, so a row of logits lands in a few dozen of its 4096 bins and the 65536 LDS atomics of
+// a long row serialise on them.  Instead the first round bins LINEARLY, bin(x) = clamp(int(x s + c), 0, 4095),
+// over the range of a 4096-entry sample of the row (each thread's first load), while the rest of the row is
+// still arriving.  Any non-decreasing bin function keeps the selection exact: with `above` entries in the bins
+// over bin B and above < k <= above + hist[B], the k-th largest is the (k - above)-th largest of bin B.  A
+// second sweep over the registers re-evaluates the same fused multiply-add and files every entry of bin B or
+// higher (some k + a few dozen of them) into a small per-thread list in LDS; the candidates of bin B are then
+// ranked exactly by their integer keys, and only the listed entries see an exponential.
+// Rows the fast path does not fit (degenerate or non-finite sample range, k-th largest in the lowest bin, more
+// than RS_CAND candidates, a thread with more than RS_CAP listed entries) take the radix rounds: slow, exact.
+constexpr int RS_CAP = 16;      // listed entries per thread
+constexpr int RS_CAND = 1024;   // candidates ranked by counting
+struct RowStatsSmem {
+  int hist1[4096], hist2[1024], hist3[1024];
+  float priv[RS_CAP * 1024];    // entry j of thread t at [j * 1024 + t]
+  float cand[RS_CAND];
+  float f_rng[32], f_max[16], f_sum[16];
+  int s_wsum[16];
+  int s_bin, s_above, n_cand, flag;
+  float s_thr;
+};
 
-  uint32_t thr_key = 0;            // keeps everything
-  float thr = -INFINITY;
-  if (topk) {
-    int k = p.top_k;
+// Workgroups are persistent: workgroup b takes rows b, b + gridDim.x, ...; the loads of its next row are issued
+// as soon as the registers of the current one are no longer needed, so that they overlap the row's tail (list
+// processing, candidate ranking, reductions).
+template <int VPT, bool VEC>   // VEC: rows start on 16-byte boundaries and V is a multiple of 4
+__global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
+  extern __shared__ __align__(16) char rs_smem_raw[];
+  RowStatsSmem& sm = *(RowStatsSmem*)rs_smem_raw;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int V = p.vocab;
+  const bool topk = p.top_k > 0 && p.top_k < V;
+  constexpr int NCH = VPT / 4;
+  // element (chunk j, c) of this thread is vocabulary entry 4 (tid + 1024 j) + c; entries past V are masked to
+  // -inf before use.  Every load is unconditional (addresses clamped into the row): all of them are in flight at once.
+  float x[VPT];
+  // (The thread index is passed through an empty asm so that the per-chunk offsets and masks below are recomputed
+  // where they are used instead of being kept in registers across the whole row loop.)
+  auto load_row = [&](int row) {
+    const char* g = (const char*)(p.logits + (int64_t)row * V);   // uniform base + 32-bit byte offsets
+    int t = tid;
+    asm volatile("" : "+v"(t));
+    if (VEC) {
 #pragma unroll
-    for (int i = 0; i < VPT; ++i)
-      if (tid + 1024 * i < V) atomicAdd(&hist1[key[i] >> 20], 1);
-    __syncthreads();
-    find_bin_from_top<4>(hist1, k, tid, lane, wave, s_wsum, &s_bin, &s_above);
-    const uint32_t b1 = (uint32_t)s_bin;
-    k -= s_above;
-    __syncthreads();   // s_bin / s_above are rewritten by the next round
+      for (int j = 0; j < NCH; ++j) {
+        const float4 q = *(const float4*)(g + 4u * (unsigned)min(4 * (t + 1024 * j), V - 4));
+        x[4 * j] = q.x; x[4 * j + 1] = q.y; x[4 * j + 2] = q.z; x[4 * j + 3] = q.w;
+      }
+    } else {
 #pragma unroll
-    for (int i = 0; i < VPT; ++i)
-      if (tid + 1024 * i < V && (key[i] >> 20) == b1) atomicAdd(&hist2[(key[i] >> 10) & 1023u], 1);
-    __syncthreads();
-    find_bin_from_top<1>(hist2, k, tid, lane, wave, s_wsum, &s_bin, &s_above);
-    const uint32_t b12 = (b1 << 10) | (uint32_t)s_bin;
-    k -= s_above;
-    __syncthreads();
+      for (int i = 0; i < VPT; ++i) x[i] = *(const float*)(g + 4u * (unsigned)min(4 * (t + 1024 * (i >> 2)) + (i & 3), V - 1));
+    }
+  };
+  int row = blockIdx.x;
+  if (row < p.n_nodes) load_row(row);
+  for (; row < p.n_nodes; row += gridDim.x) {
+    const int next = row + gridDim.x;
+    if (V != VPT * 1024) {   // workgroup-uniform: a full row needs no masking
+      int t = tid;
+      asm volatile("" : "+v"(t));
 #pragma unroll
-    for (int i = 0; i < VPT; ++i)
-      if (tid + 1024 * i < V && (key[i] >> 10) == b12) atomicAdd(&hist3[key[i] & 1023u], 1);
-    __syncthreads();
-    find_bin_from_top<1>(hist3, k, tid, lane, wave, s_wsum, &s_bin, &s_above);
-    thr_key = (b12 << 10) | (uint32_t)s_bin;
-    thr = key_f32(thr_key);
-  }
-  float se = 0.f;
+      for (int i = 0; i < VPT; ++i) x[i] = 4 * (t + 1024 * (i >> 2)) + (i & 3) < V ? x[i] : -INFINITY;
+    }
 #pragma unroll
-  for (int i = 0; i < VPT; ++i) {
-    const int v = tid + 1024 * i;
-    se += (v < V && key[i] >= thr_key) ? __expf(key_f32(key[i]) - mx) : 0.f;
-  }
-  se = wave_sum(se);
-  __syncthreads();
-  if (lane == 0) fred[wave] = se;
-  __syncthreads();
-  if (tid == 0) {
-    float tot = 0.f;
-    for (int w = 0; w < 16; ++w) tot += fred[w];
-    p.row_max[row] = mx;
-    p.row_thr[row] = thr;
-    p.row_lse[row] = mx + logf(tot);
+    for (int i = 0; i < 4; ++i) sm.hist1[tid + 1024 * i] = 0;
+    if (tid == 0) { sm.n_cand = 0; sm.flag = 0; }
+
+    // ---- range of the sample (first chunk of every thread)
+    float smax = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+    float smin = INFINITY;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) smin = fminf(smin, x[c] == -INFINITY ? INFINITY : x[c]);   // padding (and -inf logits) aside
+    smax = wave_max(smax);
+    smin = -wave_max(-smin);
+    if (lane == 0) { sm.f_rng[wave] = smax; sm.f_rng[16 + wave] = smin; }
+    __syncthreads();
+    smax = sm.f_rng[0]; smin = sm.f_rng[16];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) { smax = fmaxf(smax, sm.f_rng[w]); smin = fminf(smin, sm.f_rng[16 + w]); }
+    const float bs = 4096.f / (smax - smin), bc = -smin * bs;
+    // usable: finite positive scale and offset (rules out equal, infinite or NaN sample bounds)
+    const bool fast = topk && bs > 0.f && bs < INFINITY && fabsf(bc) < INFINITY;
+
+    float mx = -INFINITY;
+    if (fast) {
+#pragma unroll
+      for (int i = 0; i < VPT; ++i) {
+        mx = fmaxf(mx, x[i]);
+        const float t = __builtin_amdgcn_fmed3f(fmaf(x[i], bs, bc), 0.f, 4095.f);
+        atomicAdd(&sm.hist1[(int)t], 1);
+        if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep the unrolled sweep from piling up temporaries
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < VPT; ++i) mx = fmaxf(mx, x[i]);
+    }
+    mx = wave_max(mx);
+    if (lane == 0) sm.f_max[wave] = mx;
+    __syncthreads();                       // maxima and every atomic of the sweep
+    mx = sm.f_max[0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) mx = fmaxf(mx, sm.f_max[w]);
+
+    float thr = -INFINITY, se = 0.f;
+    bool done = false;
+    int cnt = 0, B = 0, n_c = 0, k = p.top_k;
+    if (fast) {
+      // the -inf padding past V went to bin 0 with everything else at or below the sample's minimum
+      find_bin_from_top<4>(sm.hist1, k, tid, lane, wave, sm.s_wsum, &sm.s_bin, &sm.s_above, 0, VPT * 1024 - V);
+      B = sm.s_bin;
+      n_c = sm.hist1[B];
+      k -= sm.s_above;                     // rank of the k-th largest inside bin B, 1 = largest
+      if (B > 0 && n_c <= RS_CAND) {       // workgroup-uniform
+        const float Bf = (float)B;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+          if (fmaf(x[i], bs, bc) >= Bf) {  // bin(x) >= B (B >= 1: the clamp at 0 plays no part; the one at 4095 cannot matter)
+            if (cnt < RS_CAP) sm.priv[cnt * 1024 + tid] = x[i];
+            ++cnt;
+          }
+          if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+        if (cnt > RS_CAP) sm.flag = 1;
+        __syncthreads();
+        done = sm.flag == 0;
+      }
+    }
+    // The registers are free (the rounds below re-read the row): the next row arrives during this row's tail.
+    if (next < p.n_nodes) load_row(next);
+    if (done) {
+      // listed entries: above bin B -> kept; in bin B -> candidate
+      const float B1f = (float)(B + 1);
+      for (int j = 0; j < cnt; ++j) {
+        const float xv = sm.priv[j * 1024 + tid];
+        if (B < 4095 && fmaf(xv, bs, bc) >= B1f) se += __expf(xv - mx);
+        else sm.cand[atomicAdd(&sm.n_cand, 1)] = xv;
+      }
+      __syncthreads();
+      // exact k-th largest of the n_c candidates by counting (ties: lower list index first); wave w ranks
+      // candidates w, w + 16, ..., its lanes share the comparisons
+      for (int i = wave; i < n_c; i += 16) {
+        const uint32_t ki = f32_key(sm.cand[i]);
+        int rank = 0;
+        for (int j = lane; j < n_c; j += 64) {
+          const uint32_t kj = f32_key(sm.cand[j]);
+          rank += (kj > ki || (kj == ki && j < i)) ? 1 : 0;
+        }
+        rank = wave_sum_i(rank);
+        if (lane == 0 && rank == k - 1) sm.s_thr = key_f32(ki);
+      }
+      __syncthreads();
+      thr = sm.s_thr;
+      const uint32_t tk = f32_key(thr);
+      for (int i = tid; i < n_c; i += 1024) {
+        const float xi = sm.cand[i];
+        if (f32_key(xi) >= tk) se += __expf(xi - mx);
+      }
+    } else {
+      // Radix rounds on the order-preserving keys (also: no top-k -> every entry kept).  Slow and exact: the row
+      // is read again from memory (mostly the caches) in every round, a few registers at a time.
+      const float* g = p.logits + (int64_t)row * V;
+      uint32_t thr_key = 0;
+      se = 0.f;
+      if (topk) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sm.hist1[tid + 1024 * i] = 0;
+        sm.hist2[tid] = 0;
+        sm.hist3[tid] = 0;
+        __syncthreads();
+        k = p.top_k;
+        for (int v = tid; v < V; v += 1024) atomicAdd(&sm.hist1[f32_key(g[v]) >> 20], 1);
+        __syncthreads();
+        find_bin_from_top<4>(sm.hist1, k, tid, lane, wave, sm.s_wsum, &sm.s_bin, &sm.s_above, 0, 0);
+        const uint32_t b1 = (uint32_t)sm.s_bin;
+        k -= sm.s_above;
+        __syncthreads();   // s_bin / s_above are rewritten by the next round
+        for (int v = tid; v < V; v += 1024) {
+          const uint32_t key = f32_key(g[v]);
+          if ((key >> 20) == b1) atomicAdd(&sm.hist2[(key >> 10) & 1023u], 1);
+        }
+        __syncthreads();
+        find_bin_from_top<1>(sm.hist2, k, tid, lane, wave, sm.s_wsum, &sm.s_bin, &sm.s_above, 0, 0);
+        const uint32_t b12 = (b1 << 10) | (uint32_t)sm.s_bin;
+        k -= sm.s_above;
+        __syncthreads();
+        for (int v = tid; v < V; v += 1024) {
+          const uint32_t key = f32_key(g[v]);
+          if ((key >> 10) == b12) atomicAdd(&sm.hist3[key & 1023u], 1);
+        }
+        __syncthreads();
+        find_bin_from_top<1>(sm.hist3, k, tid, lane, wave, sm.s_wsum, &sm.s_bin, &sm.s_above, 0, 0);
+        thr_key = (b12 << 10) | (uint32_t)sm.s_bin;
+        thr = key_f32(thr_key);
+      }
+      for (int v = tid; v < V; v += 1024) {
+        const float xv = g[v];
+        se += f32_key(xv) >= thr_key ? __expf(xv - mx) : 0.f;
+      }
+    }
+    se = wave_sum(se);
+    if (lane == 0) sm.f_sum[wave] = se;
+    __syncthreads();
+    if (tid == 0) {
+      float tot = 0.f;
+      for (int w = 0; w < 16; ++w) tot += sm.f_sum[w];
+      p.row_max[row] = mx;
+      p.row_thr[row] = thr;
+      p.row_lse[row] = mx + logf(tot);
+    }
   }
 }
 
@@ -679,13 +820,28 @@ hipError_t launch_pack_w(cascade_ctx* ctx, const void* w, int vocab, int hidden,
   return hipGetLastError();
 }
 
-hipError_t launch_row_stats(cascade_ctx* ctx, const lmhead_args* a) {
-  hipStream_t stream = ctx->stream;
+template <int VPT, bool VEC>
+hipError_t launch_row_stats_t(cascade_ctx* ctx, const LmParams& p) {
+  const size_t smem = sizeof(RowStatsSmem);
+  static bool attr_done = false;   // one flag per template instance
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)row_stats_kernel<VPT, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
   KernelTimer t(ctx, CASCADE_K_ROW_STATS);
+  // one workgroup per compute unit at most (its 1024 threads hold a row in registers), each walking its share of the rows
+  const int grid = p.n_nodes < ctx->n_cu ? p.n_nodes : ctx->n_cu;
+  CASCADE_TIMED_LAUNCH(t, (row_stats_kernel<VPT, VEC>), dim3(grid), dim3(1024), smem, ctx->stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_row_stats(cascade_ctx* ctx, const lmhead_args* a) {
   LmParams p = make_params(a);
   const int V = a->vocab;
-  if (V <= 4096) CASCADE_TIMED_LAUNCH(t, row_stats_kernel<4>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
-  else if (V <= 16384) CASCADE_TIMED_LAUNCH(t, row_stats_kernel<16>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
-  else CASCADE_TIMED_LAUNCH(t, row_stats_kernel<64>, dim3(a->n_nodes), dim3(1024), 0, stream, p);
-  return hipGetLastError();
+  // 16-byte loads need every row to start on a 16-byte boundary
+  const bool vec = V % 4 == 0 && ((uintptr_t)a->logits & 15u) == 0;
+  if (V <= 4096) return vec ? launch_row_stats_t<4, true>(ctx, p) : launch_row_stats_t<4, false>(ctx, p);
+  if (V <= 16384) return vec ? launch_row_stats_t<16, true>(ctx, p) : launch_row_stats_t<16, false>(ctx, p);
+  return vec ? launch_row_stats_t<64, true>(ctx, p) : launch_row_stats_t<64, false>(ctx, p);
 }

@@ -208,9 +208,11 @@ def test_rows_with_outliers():
 
 @pytest.mark.parametrize("case", ["plain", "ragged_vocab", "all_equal_row", "ties_at_threshold", "huge_k", "outliers"])
 def test_row_statistics_of_long_rows(case):
-    """Rows of more than 16384 entries take the compacted path (candidates above the first histogram
-    round's bin edge) unless the candidate set is too large; every variant must select exactly the k-th
-    largest of the GPU's own logits."""
+    """Rows of more than 16384 entries (64 values per thread): the linear-bin fast path (plain, ragged_vocab)
+    and every way out of it into the radix rounds - a degenerate sample range (all_equal_row), more
+    candidates in the k-th largest's bin than the ranking takes (ties_at_threshold), more listed entries per
+    thread than the lists hold (huge_k), a range stretched by outliers.  Every variant must select exactly
+    the k-th largest of the GPU's own logits."""
     rng = np.random.default_rng(21)
     vocab = 65536 - 512 if case == "ragged_vocab" else 65536
     top_k = 40000 if case == "huge_k" else 2000
