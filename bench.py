@@ -28,16 +28,37 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM traffic per launch from rocprofv3 --pmc runs of this file: (FETCH_SIZE, WRITE_SIZE) in KiB per
-# dispatch, copied from the tracked counter summaries (a CPU test compares this table with the
-# "TRAFFIC" lines of those summaries).  Bytes = FETCH x 2.0 + WRITE x 1.0: the read counter sees half
-# of the bytes that 16-byte-per-lane loads move, as the same counter shows for a streaming read of
-# known size in the same runs; writes count 1.0.  No entry = no counter run = traffic null.
+# dispatch, copied from the tracked counter summaries profiles/<workload>_step_counters.md (a CPU test
+# compares this table with the "TRAFFIC" lines of those summaries).  Bytes = FETCH x 2.0 + WRITE x 1.0:
+# the read counter sees half of the bytes that 16-byte-per-lane loads move, as the same counter shows
+# for a streaming read of known size in the same runs; writes count 1.0.  No entry = no counter run =
+# traffic null.
 FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
 MEASURED_TRAFFIC_KIB = {
-    ("janus_pro_7b", "lmhead"): (69916.2, 3840.0),
-    ("janus_pro_7b", "attn"): (6516.0, 1080.0),
-    ("janus_pro_7b", "row_stats"): (1981.0, 5.6),
+    ("stress_1024px", "accept"): (17635.8, 192.6),
+    ("stress_1024px", "attn"): (293581.2, 18432.0),
+    ("stress_1024px", "lmhead"): (792757.3, 262144.0),
+    ("stress_1024px", "pack_h"): (13974.7, 27927.3),
+    ("stress_1024px", "row_stats"): (131196.9, 101.2),
+    ("stress_1024px", "select"): (588.3, 0.9),
+    ("janus_batched", "accept"): (7515.2, 84.4),
+    ("janus_batched", "attn"): (49759.7, 8118.2),
+    ("janus_batched", "lmhead"): (98408.1, 28864.0),
+    ("janus_batched", "pack_h"): (5026.5, 10984.7),
+    ("janus_batched", "row_stats"): (14508.0, 42.3),
+    ("janus_batched", "select"): (424.0, 1.4),
     ("janus_pro_7b", "accept"): (974.7, 11.2),
+    ("janus_pro_7b", "attn"): (6521.0, 1080.0),
+    ("janus_pro_7b", "lmhead"): (70017.2, 3840.0),
+    ("janus_pro_7b", "pack_h"): (1969.6, 3979.6),
+    ("janus_pro_7b", "row_stats"): (1996.0, 5.6),
+    ("janus_pro_7b", "select"): (52.8, 0.2),
+    ("lumina_mgpt_7b_768", "accept"): (983.3, 11.2),
+    ("lumina_mgpt_7b_768", "attn"): (22158.7, 1080.0),
+    ("lumina_mgpt_7b_768", "lmhead"): (269929.2, 15360.0),
+    ("lumina_mgpt_7b_768", "pack_h"): (6438.0, 12916.4),
+    ("lumina_mgpt_7b_768", "row_stats"): (7803.6, 5.6),
+    ("lumina_mgpt_7b_768", "select"): (144.2, 0.2),
 }
 
 
@@ -165,10 +186,37 @@ def tau_sweep(args) -> int:
         assert ds.ctx.device_status() == binding.OK
         ds.w = None
         del ds
+    # the cost the accepted tokens are bought with: the WHOLE step (attention, projection, statistics, acceptance,
+    # walk) of the full stress configuration (4200-key prefixes), timed per threshold on rotating input copies
+    inp = wl.make_config(4, 0, w=w0)
+    ds = binding.DeviceStep(inp)
+    kcs = [ds.k_cache] + [ds.k_cache.clone() for _ in range(3)]
+    vcs = [ds.v_cache] + [ds.v_cache.clone() for _ in range(3)]
+    ws = [w_packed] + [w_packed.clone() for _ in range(3)]
+    step_us = {}
+    for t in taus:
+        def one(i):
+            ds.k_cache, ds.v_cache = kcs[i % 4], vcs[i % 4]
+            ds.attn()
+            ds.lmhead(ws[i % 4], binding.W_PACKED32)
+            ds.accept(t, t)
+            ds.select()
+        for i in range(5):
+            one(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(40):
+            one(i)
+        torch.cuda.synchronize()
+        step_us[t] = (time.perf_counter() - t0) * 1e6 / 40
+    assert ds.ctx.device_status() == binding.OK
     out = {"metric": "tau_sweep", "tokens": "rank-zipf of the parent's logits" if args.rank_zipf else "generator's tokens",
-           "workload": "stress_1024px trees (prefix cut to 64), seeds 0..%d" % (args.sweep_seeds - 1),
+           "workload": "stress_1024px trees (prefix cut to 64), seeds 0..%d; whole-step time on the full configuration" % (args.sweep_seeds - 1),
            "per_tau": {str(t): {"mean_accept_len": float(np.mean(acc_len[t])), "accept_us": float(np.mean(acc_us[t])),
-                                "select_us": float(np.mean(sel_us[t])), "prompts": len(acc_len[t])} for t in taus}}
+                                "select_us": float(np.mean(sel_us[t])), "prompts": len(acc_len[t]),
+                                "whole_step_us": step_us[t],
+                                "accepted_tokens_per_s": float(np.mean(acc_len[t])) * inp.n_prompts / (step_us[t] * 1e-6)}
+                       for t in taus}}
     print(json.dumps(out))
     return 0
 

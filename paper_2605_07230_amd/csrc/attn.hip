@@ -1525,25 +1525,33 @@ hipError_t launch_tree_attn_f32(cascade_ctx* ctx, const tree_attn_args* a) {
   return hipGetLastError();
 }
 
-template <int D, int NKG>
+// CAN_SPLIT: the dispatcher may split the keys across workgroups for this instantiation (it never does when
+// there are two or more workgroups per compute unit anyway, so those partial-writing variants are not built)
+template <int D, int NKG, bool CAN_SPLIT>
 hipError_t launch_ksplit_t(cascade_ctx* ctx, AttnParams& p, dim3 grid) {
   hipStream_t st = ctx->stream;
   const size_t smem = NKG * sizeof(KsplitGroupSmem<D>) + CASCADE_MAX_TREE * sizeof(int) + NKG * 64 * sizeof(unsigned long long);
   static_assert(NKG * 64 * (D + 4) * 4 + NKG * 64 * 2 * 4 <= NKG * sizeof(KsplitGroupSmem<D>), "merge buffers fit in the tile buffers");
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_ksplit_kernel<D, NKG, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_bf16_ksplit_kernel<D, NKG, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_ksplit_kernel<D, NKG, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if constexpr (CAN_SPLIT) {
+      if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_bf16_ksplit_kernel<D, NKG, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    }
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   if (p.n_split > 1) {
-    {
-      KernelTimer t(ctx, CASCADE_K_ATTN);
-      CASCADE_TIMED_LAUNCH(t, (attn_bf16_ksplit_kernel<D, NKG, true>), grid, dim3(NKG * 256), smem, st, p);
+    if constexpr (CAN_SPLIT) {
+      {
+        KernelTimer t(ctx, CASCADE_K_ATTN);
+        CASCADE_TIMED_LAUNCH(t, (attn_bf16_ksplit_kernel<D, NKG, true>), grid, dim3(NKG * 256), smem, st, p);
+      }
+      KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
+      CASCADE_TIMED_LAUNCH(t, (attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
+    } else {
+      return hipErrorInvalidValue;   // the dispatcher never asks for it
     }
-    KernelTimer t(ctx, CASCADE_K_ATTN_MERGE);
-    CASCADE_TIMED_LAUNCH(t, (attn_merge_kernel<D>), dim3((p.n_rows_total + (1024 / D) - 1) / (1024 / D)), dim3(256), 0, st, p);
   } else {
     KernelTimer t(ctx, CASCADE_K_ATTN);
     CASCADE_TIMED_LAUNCH(t, (attn_bf16_ksplit_kernel<D, NKG, false>), grid, dim3(NKG * 256), smem, st, p);
@@ -1599,8 +1607,9 @@ hipError_t launch_tree_attn_bf16(cascade_ctx* ctx, const tree_attn_args* a) {
     // workgroups are scarce; half as many when there are at least two per CU anyway - smaller workgroups,
     // four resident per CU, hide each other's tile latencies better (54 -> 46 us at 16 rows x 32 heads)
     const bool many = base_wgs >= 512;
-    if (a->head_dim == 128) return many ? launch_ksplit_t<128, 1>(ctx, p, grid) : launch_ksplit_t<128, 2>(ctx, p, grid);
-    return many ? launch_ksplit_t<64, 2>(ctx, p, grid) : launch_ksplit_t<64, 4>(ctx, p, grid);
+    // (many => fill == 1 => n_split == 1 above)
+    if (a->head_dim == 128) return many ? launch_ksplit_t<128, 1, false>(ctx, p, grid) : launch_ksplit_t<128, 2, true>(ctx, p, grid);
+    return many ? launch_ksplit_t<64, 2, false>(ctx, p, grid) : launch_ksplit_t<64, 4, true>(ctx, p, grid);
   }
   // large trees: NW waves x 2 query blocks each share every K/V tile through LDS
   // (measured at 8 rows x 32 heads x 256 nodes, 4200-key prefix: 283 us with 4 waves x 4 blocks and
