@@ -517,8 +517,9 @@ __device__ __forceinline__ void find_bin_from_top(const int* hist, int k, int ti
 // ranked exactly by their integer keys, and only the listed entries see an exponential.
 // Rows the fast path does not fit (degenerate or non-finite sample range, k-th largest in the lowest bin, more
 // than RS_CAND candidates, a thread with more than RS_CAP listed entries) take the radix rounds: slow, exact.
-constexpr int RS_CAP = 16;      // listed entries per thread
+constexpr int RS_CAP = 12;      // listed entries per thread
 constexpr int RS_CAND = 1024;   // candidates ranked by counting
+constexpr int RS_PRE_OFFSET = 80 * 1024;   // 80 KiB prefetch buffer behind the structure below (1 KiB aligned)
 struct RowStatsSmem {
   int hist1[4096], hist2[1024], hist3[1024];
   float priv[RS_CAP * 1024];    // entry j of thread t at [j * 1024 + t]
@@ -534,14 +535,25 @@ struct RowStatsSmem {
 // processing, candidate ranking, reductions).
 template <int VPT, bool VEC>   // VEC: rows start on 16-byte boundaries and V is a multiple of 4
 __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
-  extern __shared__ __align__(16) char rs_smem_raw[];
+  extern __shared__ __align__(1024) char rs_smem_raw[];
   RowStatsSmem& sm = *(RowStatsSmem*)rs_smem_raw;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int V = p.vocab;
   const bool topk = p.top_k > 0 && p.top_k < V;
   constexpr int NCH = VPT / 4;
-  // element (chunk j, c) of this thread is vocabulary entry 4 (tid + 1024 j) + c; entries past V are masked to
-  // -inf before use.  Every load is unconditional (addresses clamped into the row): all of them are in flight at once.
+  // Long rows: the first NPRE 16 KiB chunks of the NEXT row are fetched into LDS (LDS-direct loads, no registers
+  // needed) while the current row's registers are still in use - HBM would otherwise idle between the end of a
+  // row's loads and the moment its registers are free.  A thread reads back exactly the 16 bytes its own lane
+  // fetched, so no barrier is involved.
+  constexpr int NPRE = (VEC && VPT == 64) ? 5 : 0;
+  constexpr int NREG = NCH - NPRE;   // chunks loaded into registers
+  float* const pre = (float*)(rs_smem_raw + RS_PRE_OFFSET);
+  const unsigned pre_lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)pre) + 1024u * (unsigned)__builtin_amdgcn_readfirstlane(wave);
+  // x-chunk jj of this thread holds memory chunk mch(jj): the register-loaded chunks first (they are swept in the
+  // order they arrive), the chunks that come from LDS last.  Element (memory chunk m, c) is vocabulary entry
+  // 4 (tid + 1024 m) + c; entries past V are masked to -inf before use.  Every load is unconditional (addresses
+  // clamped into the row): all of them are in flight at once.
+  auto mch = [](int jj) { return jj < NREG ? jj + NPRE : jj - NREG; };
   float x[VPT];
   // (The thread index is passed through an empty asm so that the per-chunk offsets and masks below are recomputed
   // where they are used instead of being kept in registers across the whole row loop.)
@@ -551,25 +563,44 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
     asm volatile("" : "+v"(t));
     if (VEC) {
 #pragma unroll
-      for (int j = 0; j < NCH; ++j) {
-        const float4 q = *(const float4*)(g + 4u * (unsigned)min(4 * (t + 1024 * j), V - 4));
-        x[4 * j] = q.x; x[4 * j + 1] = q.y; x[4 * j + 2] = q.z; x[4 * j + 3] = q.w;
+      for (int jj = 0; jj < NREG; ++jj) {
+        const float4 q = *(const float4*)(g + 4u * (unsigned)min(4 * (t + 1024 * mch(jj)), V - 4));
+        x[4 * jj] = q.x; x[4 * jj + 1] = q.y; x[4 * jj + 2] = q.z; x[4 * jj + 3] = q.w;
       }
     } else {
 #pragma unroll
       for (int i = 0; i < VPT; ++i) x[i] = *(const float*)(g + 4u * (unsigned)min(4 * (t + 1024 * (i >> 2)) + (i & 3), V - 1));
     }
   };
-  int row = blockIdx.x;
-  if (row < p.n_nodes) load_row(row);
-  for (; row < p.n_nodes; row += gridDim.x) {
-    const int next = row + gridDim.x;
+  auto prefetch_row = [&](int row) {   // memory chunks 0 .. NPRE-1 -> LDS, lane l's 16 bytes at 16 l behind M0
+    const char* g = (const char*)(p.logits + (int64_t)row * V);
+    int t = tid;
+    asm volatile("" : "+v"(t));
+#pragma unroll
+    for (int m = 0; m < NPRE; ++m) {
+      const unsigned voff = 4u * (unsigned)min(4 * (t + 1024 * m), V - 4);
+      const unsigned l = pre_lds + 16384u * m;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(voff), "s"(g) : "memory");
+    }
+  };
+  auto mask_chunks = [&](int jj0, int jj1) {
     if (V != VPT * 1024) {   // workgroup-uniform: a full row needs no masking
       int t = tid;
       asm volatile("" : "+v"(t));
 #pragma unroll
-      for (int i = 0; i < VPT; ++i) x[i] = 4 * (t + 1024 * (i >> 2)) + (i & 3) < V ? x[i] : -INFINITY;
+      for (int jj = jj0; jj < jj1; ++jj)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) x[4 * jj + c] = 4 * (t + 1024 * mch(jj)) + c < V ? x[4 * jj + c] : -INFINITY;
     }
+  };
+  int row = blockIdx.x;
+  if (row < p.n_nodes) {
+    prefetch_row(row);   // (the first row has nothing to hide behind: same loads, issued first)
+    load_row(row);
+  }
+  for (; row < p.n_nodes; row += gridDim.x) {
+    const int next = row + gridDim.x;
+    mask_chunks(0, NREG);
 #pragma unroll
     for (int i = 0; i < 4; ++i) sm.hist1[tid + 1024 * i] = 0;
     if (tid == 0) { sm.n_cand = 0; sm.flag = 0; }
@@ -591,17 +622,36 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
     const bool fast = topk && bs > 0.f && bs < INFINITY && fabsf(bc) < INFINITY;
 
     float mx = -INFINITY;
-    if (fast) {
+    auto sweep = [&](int jj0, int jj1) {   // row maximum and first-round histogram of x-chunks jj0 .. jj1-1
+      if (fast) {
 #pragma unroll
-      for (int i = 0; i < VPT; ++i) {
-        mx = fmaxf(mx, x[i]);
-        const float t = __builtin_amdgcn_fmed3f(fmaf(x[i], bs, bc), 0.f, 4095.f);
-        atomicAdd(&sm.hist1[(int)t], 1);
-        if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep the unrolled sweep from piling up temporaries
+        for (int i = 4 * jj0; i < 4 * jj1; ++i) {
+          mx = fmaxf(mx, x[i]);
+          const float t = __builtin_amdgcn_fmed3f(fmaf(x[i], bs, bc), 0.f, 4095.f);
+          atomicAdd(&sm.hist1[(int)t], 1);
+          if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep the unrolled sweep from piling up temporaries
+        }
+      } else {
+#pragma unroll
+        for (int i = 4 * jj0; i < 4 * jj1; ++i) mx = fmaxf(mx, x[i]);
       }
-    } else {
+    };
+    sweep(0, NREG);
+    if (NPRE > 0) {
+      // every load of this row that went to registers has been waited for; the LDS-direct ones were issued before
+      // them and complete in order - waited for explicitly all the same
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      int t = tid;
+      asm volatile("" : "+v"(t));
 #pragma unroll
-      for (int i = 0; i < VPT; ++i) mx = fmaxf(mx, x[i]);
+      for (int m = 0; m < NPRE; ++m) {
+        const float4 q = *(const float4*)(pre + 4096 * m + 4 * t);
+        x[4 * (NREG + m)] = q.x; x[4 * (NREG + m) + 1] = q.y; x[4 * (NREG + m) + 2] = q.z; x[4 * (NREG + m) + 3] = q.w;
+      }
+      mask_chunks(NREG, NCH);
+      sweep(NREG, NCH);
+      // the values are in registers (the sweep consumed them): the buffer can take the next row's chunks
+      if (next < p.n_nodes) prefetch_row(next);
     }
     mx = wave_max(mx);
     if (lane == 0) sm.f_max[wave] = mx;
@@ -822,7 +872,8 @@ hipError_t launch_pack_w(cascade_ctx* ctx, const void* w, int vocab, int hidden,
 
 template <int VPT, bool VEC>
 hipError_t launch_row_stats_t(cascade_ctx* ctx, const LmParams& p) {
-  const size_t smem = sizeof(RowStatsSmem);
+  static_assert(sizeof(RowStatsSmem) <= RS_PRE_OFFSET, "the prefetch buffer starts behind the structure");
+  const size_t smem = (VEC && VPT == 64) ? RS_PRE_OFFSET + 80 * 1024 : sizeof(RowStatsSmem);
   static bool attr_done = false;   // one flag per template instance
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)row_stats_kernel<VPT, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

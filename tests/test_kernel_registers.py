@@ -74,3 +74,15 @@ def test_ring_attention_m0_and_waits(tmp_path):
         inline = re.findall(r";;#ASMSTART\n(.*?);;#ASMEND", body, flags=re.S)
         ops = {l.split()[0] for blk in inline for l in blk.strip().splitlines()}
         assert ops <= {"s_waitcnt", "s_barrier", "s_mov_b32", "s_nop", "global_load_lds_dwordx4"}, (name, ops)
+
+
+def test_row_statistics_prefetch_uses_m0_only_for_its_loads(tmp_path):
+    """The long-row statistics kernel prefetches part of the next row with LDS-direct loads (M0 set by hand,
+    the compiler is not told): nothing else in that kernel may touch M0."""
+    _, text = _kernel_stats("lmhead.hip", tmp_path)
+    bodies = re.findall(r"^(_ZN\S*row_stats_kernelILi64ELb1E\S*):[^\n]*\n(.*?)\.amdhsa_kernel", text, flags=re.S | re.M)
+    assert len(bodies) == 1
+    name, body = bodies[0]
+    m0 = [l.strip() for l in body.splitlines() if re.search(r"\bm0\b", l)]
+    assert m0 and all(l.startswith("s_mov_b32 m0,") for l in m0), (name, m0[:5])
+    assert body.count("global_load_lds_dwordx4") >= 8 and "scratch_" not in body
