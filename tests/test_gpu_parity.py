@@ -247,6 +247,21 @@ def test_f32_ragged_batch():
     pu.check_accept_and_path(inp, ds)
 
 
+@pytest.mark.parametrize("vocab,top_k", [(5001, 100), (16390, 300), (16390, 1), (16390, 16389), (20000, 0)])
+def test_f32_row_lengths_that_are_not_multiples_of_four(vocab, top_k):
+    """fp32 logits rows of arbitrary length take the statistics kernels' scalar-load instantiations
+    (16 and 64 values per thread), with the top-k bound at both ends and switched off."""
+    rng = np.random.default_rng(vocab + top_k)
+    inp = _small_bf16(31, dtype="f32", head_dim=32, hidden=64, vocab=vocab, top_k=top_k, n_prompts=1, prefix_lens=[6, 6],
+                      trees=[wl.grow_tree(rng, 9, 3, 3)])
+    ds = pu.run_gpu_step(inp)
+    pu.check_lmhead(inp, ds)
+    if 0 < top_k < vocab:
+        g = ds.logits.cpu().numpy()
+        kept = (g >= ds.row_thr.cpu().numpy()[:, None]).sum(axis=1)
+        assert (kept >= top_k).all() and (kept <= top_k + 8).all()
+
+
 def test_argument_validation_enqueues_nothing():
     inp = wl.make_config(0, 0)
     ds = binding.DeviceStep(inp)
