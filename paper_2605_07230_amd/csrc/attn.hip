@@ -131,17 +131,38 @@ constexpr int KT = 64;  // keys per tile
 // is almost done and finish alone.  Dispatch position z therefore takes the z-th heaviest row
 // (keys = prefix + tree nodes; ties by index), computed redundantly by every wave from the two small
 // arrays it reads anyway.  Batches of more than 64 rows keep their order.
-__device__ __forceinline__ int row_by_work_rank(const AttnParams& p, int z, int n_rows, int lane) {
-  if (n_rows > 64 || n_rows <= 1) return z;
-  int work = -1;
-  if (lane < n_rows) work = p.prefix_len[lane] + (p.node_off[lane + 1] - p.node_off[lane]);
+// The row's first node, node count and prefix length come back with it: the lanes already hold them, so the
+// workgroup does not go to memory a second time for three values that the next loads depend on.
+struct RowInfo {
+  int s, lo, T, P;
+};
+__device__ __forceinline__ RowInfo row_by_work_rank(const AttnParams& p, int z, int n_rows, int lane) {
+  RowInfo ri;
+  if (n_rows > 64 || n_rows <= 1) {
+    ri.s = z;
+    ri.lo = p.node_off[z];
+    ri.T = p.node_off[z + 1] - ri.lo;
+    ri.P = p.prefix_len[z];
+    return ri;
+  }
+  int lo_l = 0, t_l = 0, p_l = 0, work = -1;
+  if (lane < n_rows) {
+    lo_l = p.node_off[lane];
+    t_l = p.node_off[lane + 1] - lo_l;
+    p_l = p.prefix_len[lane];
+    work = p_l + t_l;
+  }
   int rank = 0;
   for (int r = 0; r < n_rows; ++r) {
     const int wr = __builtin_amdgcn_readlane(work, r);
     rank += (wr > work || (wr == work && r < lane)) ? 1 : 0;
   }
   const unsigned long long hit = __ballot(lane < n_rows && rank == z);
-  return hit ? __ffsll((long long)hit) - 1 : z;
+  ri.s = hit ? __ffsll((long long)hit) - 1 : z;   // (ranks are a permutation: some lane always hits)
+  ri.lo = __builtin_amdgcn_readlane(lo_l, ri.s);
+  ri.T = __builtin_amdgcn_readlane(t_l, ri.s);
+  ri.P = __builtin_amdgcn_readlane(p_l, ri.s);
+  return ri;
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs (one L2 each) in launch order: hardware id h runs on
@@ -232,11 +253,9 @@ __global__ __launch_bounds__(64 * NW, (NQ == 4 || NW == 8) ? 1 : 2) void attn_bf
   const unsigned nx = gridDim.x, ny = gridDim.y;
   const unsigned lid = xcd_local_order(blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z), nx, ny * gridDim.z);
   const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny);
-  const int s = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, threadIdx.x & 63);
+  const RowInfo ri = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, threadIdx.x & 63);
+  const int s = ri.s, lo = ri.lo, T = ri.T, P = ri.P;
   const int split = bx % p.n_split, sb = bx / p.n_split;
-  const int lo = p.node_off[s];
-  const int T = p.node_off[s + 1] - lo;
-  const int P = p.prefix_len[s];
   const int G = p.group;
   const int M = T * G;
   const int row0 = sb * RW;
@@ -554,11 +573,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_ring_kernel(AttnParams p) {
   const unsigned nx = gridDim.x, ny = gridDim.y;
   const unsigned lid = xcd_local_order(blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z), nx, ny * gridDim.z);
   const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny);
-  const int s = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, lane);
+  const RowInfo ri = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, lane);
+  const int s = ri.s, lo = ri.lo, T = ri.T, P = ri.P;
   const int sb = bx;   // the keys of a row are never split across workgroups here (n_split == 1)
-  const int lo = p.node_off[s];
-  const int T = p.node_off[s + 1] - lo;
-  const int P = p.prefix_len[s];
   const int G = p.group;
   const int M = T * G;
   const int row0 = sb * RW;
@@ -913,11 +930,9 @@ __global__ __launch_bounds__(NKG * 256, (NKG == 1 ? 3 : 1)) void attn_bf16_kspli
   const unsigned nx = gridDim.x, ny = gridDim.y;
   const unsigned lid = xcd_local_order(blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z), nx, ny * gridDim.z);
   const int bx = (int)(lid % nx), kvh = (int)((lid / nx) % ny);
-  const int s = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, threadIdx.x & 63);
+  const RowInfo ri = row_by_work_rank(p, (int)(lid / (nx * ny)), (int)gridDim.z, threadIdx.x & 63);
+  const int s = ri.s, lo = ri.lo, T = ri.T, P = ri.P;
   const int split = bx % p.n_split, sb = bx / p.n_split;
-  const int lo = p.node_off[s];
-  const int T = p.node_off[s + 1] - lo;
-  const int P = p.prefix_len[s];
   const int G = p.group;
   const int M = T * G;
   const int row0 = sb * 64;
@@ -1104,8 +1119,38 @@ __global__ __launch_bounds__(NKG * 256, (NKG == 1 ? 3 : 1)) void attn_bf16_kspli
     }
   }
 
-  // merge the four key groups through LDS (the tile buffers are reused)
   l_run = rows4_sum(l_run);
+  if (NKG == 1) {
+    // one key group: nothing to merge - every wave writes its 16 rows from its registers (lane (l16, g) owns
+    // d = 16 db + 4 g + c of query l16), no LDS round trip and no barrier
+    if (q_ok) {
+      const int i = qr % T, hg = qr / T;
+      const int64_t rowg = (int64_t)(lo + i) * p.n_heads + kvh * G + hg;
+      if (SPLIT) {
+        float* wo = p.ws_o + ((int64_t)split * p.n_rows_total + rowg) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) *(f32x4*)(wo + 16 * db + 4 * g) = ot[db];
+        if (g == 0) {
+          float* wm = p.ws_ml + ((int64_t)split * p.n_rows_total + rowg) * 2;
+          wm[0] = m_run;
+          wm[1] = l_run;
+        }
+      } else {
+        const float inv = 1.f / l_run;
+        uint16_t* op = (uint16_t*)p.out + rowg * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          uint2 w2;
+          w2.x = pack_bf16x2(ot[db][0] * inv, ot[db][1] * inv);
+          w2.y = pack_bf16x2(ot[db][2] * inv, ot[db][3] * inv);
+          *(uint2*)(op + 16 * db + 4 * g) = w2;
+        }
+        if (g == 0 && p.lse) p.lse[rowg] = m_run * LN2 + logf(l_run);
+      }
+    }
+    return;
+  }
+  // merge the key groups through LDS (the tile buffers are reused)
   __syncthreads();
   float* mo = (float*)smem_raw;                 // [NKG][64 rows][OP]
   float* mml = mo + NKG * 64 * OP;              // [NKG][64 rows][2]
