@@ -541,7 +541,7 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
   const int V = p.vocab;
   const bool topk = p.top_k > 0 && p.top_k < V;
   constexpr int NCH = VPT / 4;
-  // Long rows: the first NPRE 16 KiB chunks of the NEXT row are fetched into LDS (LDS-direct loads, no registers
+  // Long rows: the last NPRE 16 KiB chunks of the NEXT row are fetched into LDS (LDS-direct loads, no registers
   // needed) while the current row's registers are still in use - HBM would otherwise idle between the end of a
   // row's loads and the moment its registers are free.  A thread reads back exactly the 16 bytes its own lane
   // fetched, so no barrier is involved.
@@ -549,11 +549,11 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
   constexpr int NREG = NCH - NPRE;   // chunks loaded into registers
   float* const pre = (float*)(rs_smem_raw + RS_PRE_OFFSET);
   const unsigned pre_lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)pre) + 1024u * (unsigned)__builtin_amdgcn_readfirstlane(wave);
-  // x-chunk jj of this thread holds memory chunk mch(jj): the register-loaded chunks first (they are swept in the
-  // order they arrive), the chunks that come from LDS last.  Element (memory chunk m, c) is vocabulary entry
-  // 4 (tid + 1024 m) + c; entries past V are masked to -inf before use.  Every load is unconditional (addresses
-  // clamped into the row): all of them are in flight at once.
-  auto mch = [](int jj) { return jj < NREG ? jj + NPRE : jj - NREG; };
+  // Chunk jj of this thread, element c, is vocabulary entry 4 (tid + 1024 jj) + c: chunks 0 .. NREG-1 are loaded
+  // into registers (and swept in the order they arrive; chunk 0, always inside the row, is the sample), chunks
+  // NREG .. NCH-1 come from LDS and are swept last.  Entries past V are masked to -inf before use.  Every load
+  // is unconditional (addresses clamped into the row): all of them are in flight at once.
+  auto mch = [](int jj) { return jj; };
   float x[VPT];
   // (The thread index is passed through an empty asm so that the per-chunk offsets and masks below are recomputed
   // where they are used instead of being kept in registers across the whole row loop.)
@@ -572,13 +572,13 @@ __global__ __launch_bounds__(1024) void row_stats_kernel(LmParams p) {
       for (int i = 0; i < VPT; ++i) x[i] = *(const float*)(g + 4u * (unsigned)min(4 * (t + 1024 * (i >> 2)) + (i & 3), V - 1));
     }
   };
-  auto prefetch_row = [&](int row) {   // memory chunks 0 .. NPRE-1 -> LDS, lane l's 16 bytes at 16 l behind M0
+  auto prefetch_row = [&](int row) {   // chunks NREG .. NCH-1 -> LDS, lane l's 16 bytes at 16 l behind M0
     const char* g = (const char*)(p.logits + (int64_t)row * V);
     int t = tid;
     asm volatile("" : "+v"(t));
 #pragma unroll
     for (int m = 0; m < NPRE; ++m) {
-      const unsigned voff = 4u * (unsigned)min(4 * (t + 1024 * m), V - 4);
+      const unsigned voff = 4u * (unsigned)min(4 * (t + 1024 * (NREG + m)), V - 4);
       const unsigned l = pre_lds + 16384u * m;
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(voff), "s"(g) : "memory");
     }

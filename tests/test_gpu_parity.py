@@ -206,7 +206,8 @@ def test_rows_with_outliers():
     assert (kept >= 300).all() and (kept <= 310).all()
 
 
-@pytest.mark.parametrize("case", ["plain", "ragged_vocab", "all_equal_row", "ties_at_threshold", "huge_k", "outliers"])
+@pytest.mark.parametrize("case", ["plain", "ragged_vocab", "all_equal_row", "ties_at_threshold", "huge_k", "outliers", "k_one",
+                                  "k_all_but_one", "barely_long"])
 def test_row_statistics_of_long_rows(case):
     """Rows of more than 16384 entries (64 values per thread): the linear-bin fast path (plain, ragged_vocab)
     and every way out of it into the radix rounds - a degenerate sample range (all_equal_row), more
@@ -214,8 +215,9 @@ def test_row_statistics_of_long_rows(case):
     thread than the lists hold (huge_k), a range stretched by outliers.  Every variant must select exactly
     the k-th largest of the GPU's own logits."""
     rng = np.random.default_rng(21)
-    vocab = 65536 - 512 if case == "ragged_vocab" else 65536
-    top_k = 40000 if case == "huge_k" else 2000
+    # barely_long: 18432 entries - the chunk that serves as the sample lies wholly past the end of the row
+    vocab = {"ragged_vocab": 65536 - 512, "barely_long": 18432}.get(case, 65536)
+    top_k = {"huge_k": 40000, "k_one": 1, "k_all_but_one": vocab - 1}.get(case, 2000)
     print(f"[long rows] {case}", flush=True)
     inp = _small_bf16(21, n_prompts=1, prefix_lens=[8, 8], trees=[wl.grow_tree(rng, 10, 3, 4)], hidden=128, vocab=vocab,
                       top_k=top_k, align=0.0)
@@ -231,7 +233,7 @@ def test_row_statistics_of_long_rows(case):
     g = ds.logits.cpu().numpy()
     kept = (g >= ds.row_thr.cpu().numpy()[:, None]).sum(axis=1)
     assert (kept >= top_k).all()
-    if case in ("plain", "ragged_vocab", "outliers"):
+    if case in ("plain", "ragged_vocab", "outliers", "k_one", "k_all_but_one", "barely_long"):
         assert (kept <= top_k + 64).all()
     if case == "all_equal_row":
         assert kept[2] == vocab
