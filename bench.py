@@ -361,6 +361,7 @@ def main() -> int:
     ap.add_argument("--other-steps", type=int, default=200)
     ap.add_argument("--copies", type=int, default=4, help="independent copies of W / KV rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-vendor-gemm", action="store_true", help="skip the vendor GEMM timed beside the tiled projection")
     ap.add_argument("--row-major-w", action="store_true", help="keep the LM-head matrix row-major (default: packed once, as at model load)")
     ap.add_argument("--cache-warm", action="store_true", help="also time the steps on one copy of the inputs (served from the last-level cache)")
     ap.add_argument("--commit-layers", type=int, default=30, help="decoder layers in the separately timed KV commit (0: skip)")
@@ -467,6 +468,30 @@ def main() -> int:
                     "ms_per_step_synchronous": lr_sync.seconds * 1e3 / max(lr_sync.steps, 1)}
         del loop
 
+    # yardstick for the tiled projection: the vendor GEMM (torch.matmul, bf16 result) on the same
+    # rows x hidden x vocab product, W rotated over two copies; it has no guidance combine and writes half
+    # the bytes.  Context only: no part of the step calls it.
+    vendor = None
+    if head["roofline"]["bound"] == "mfma" and not args.no_vendor_gemm:
+        rows_v = inp.n_nodes * (2 if inp.h_uncond is not None else 1)
+        a_v = torch.cat([ds.h_cond, ds.h_uncond]) if ds.h_uncond is not None else ds.h_cond   # the step's own rows
+        w_v = [ds.w.t(), ds.w.clone().t()]
+        for i in range(4):
+            c_v = a_v @ w_v[i % 2]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(20):
+            c_v = a_v @ w_v[i % 2]
+        e1.record()
+        torch.cuda.synchronize()
+        us_v = e0.elapsed_time(e1) * 1e3 / 20
+        tf_v = 2.0 * rows_v * inp.hidden * inp.vocab / (us_v * 1e-6) / 1e12
+        vendor = {"what": "torch.matmul bf16 [rows, hidden] x [hidden, vocab], bf16 result, no guidance combine",
+                  "us": us_v, "TFLOPs": tf_v, "frac": tf_v / MFMA_BF16_PEAK_TFLOPS,
+                  "tiled_projection_us": head["kernel_us"]["lmhead"]}
+        del a_v, w_v, c_v
+
     ds.ctx.close()
     del ds
     torch.cuda.empty_cache()
@@ -498,6 +523,7 @@ def main() -> int:
         "kv_commit": commit,
         "convergence_weights": weights,
         "decode_loop": loop_out,
+        "vendor_gemm_yardstick": vendor,
         "roofline": head["roofline"],
         "roofline_attention": head["roofline_attention"],
         "roofline_row_stats": head["roofline_row_stats"],

@@ -147,13 +147,20 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
   }
   if (node >= Tn) return;
   const int64_t gi = lo + node;
-  // wave 0 scans the tree for siblings and children; its first chunk (parents and tokens of nodes
-  // 0..63) is requested here, before anything waits for this node's own parent pointer
-  int pj0 = -2, tk0 = -1;
-  if (wave == 0 && lane < Tn) {
-    pj0 = a.parent[lo + lane];
-    tk0 = a.token[lo + lane];
-  }
+  // wave 0 scans the tree for siblings and children, SCAN chunks of 64 nodes per round trip; the first
+  // SCAN chunks (parents and tokens) are requested here, before anything waits for this node's own parent
+  // pointer
+  constexpr int SCAN = 4;
+  int pj0[SCAN], tk0[SCAN];
+  auto request_chunks = [&](int base) {
+#pragma unroll
+    for (int c = 0; c < SCAN; ++c) {
+      const int j = base + 64 * c + lane;
+      pj0[c] = j < Tn ? a.parent[lo + j] : -2;
+      tk0[c] = j < Tn ? a.token[lo + j] : -1;
+    }
+  };
+  if (wave == 0) request_chunks(0);
   const int par = a.parent[gi];
   auto write_zero = [&]() {
     if (tid == 0) {
@@ -173,33 +180,34 @@ __global__ __launch_bounds__(256) void accept_node_kernel(accept_args a, int* de
 
   if (wave == 0) {   // siblings (children of par, in index order, a included) and children of a
     int ks = 0, kc = 0, rank = -1;
-    for (int base = 0; base < Tn; base += 64) {   // from chunk 0: these loads do not wait for par
-      const int j = base + lane;
-      int pj = pj0, tk = tk0;
-      if (base > 0) {
-        pj = j < Tn ? a.parent[lo + j] : -2;
-        tk = j < Tn ? a.token[lo + j] : -1;
-      }
-      const bool sib = pj == par && j > par;
-      const unsigned long long sm = __ballot(sib);
-      if (sib) {
-        const int r = ks + __popcll(sm & ((1ull << lane) - 1ull));
-        if (r < MAXW) {
-          s_sib[r] = j;
-          s_stok[r] = tk;
-          // other index: parent is 0; siblings keep their rank order with a left out
-          if (j != node) s_other[1 + r - (j > node ? 1 : 0)] = j;
+    for (int base = 0; base < Tn; base += 64 * SCAN) {
+      if (base > 0) request_chunks(base);
+#pragma unroll
+      for (int c = 0; c < SCAN; ++c) {
+        if (base + 64 * c >= Tn) break;
+        const int j = base + 64 * c + lane;
+        const int pj = pj0[c], tk = tk0[c];
+        const bool sib = pj == par && j > par;
+        const unsigned long long sm = __ballot(sib);
+        if (sib) {
+          const int r = ks + __popcll(sm & ((1ull << lane) - 1ull));
+          if (r < MAXW) {
+            s_sib[r] = j;
+            s_stok[r] = tk;
+            // other index: parent is 0; siblings keep their rank order with a left out
+            if (j != node) s_other[1 + r - (j > node ? 1 : 0)] = j;
+          }
+          if (j == node) rank = r;
         }
-        if (j == node) rank = r;
+        ks += __popcll(sm);
+        const bool ch = pj == node && j > node;
+        const unsigned long long cm = __ballot(ch);
+        if (ch) {
+          const int r = kc + __popcll(cm & ((1ull << lane) - 1ull));
+          if (r < MAXW) { s_chl[r] = j; s_ctok[r] = tk; }
+        }
+        kc += __popcll(cm);
       }
-      ks += __popcll(sm);
-      const bool ch = pj == node && j > node;
-      const unsigned long long cm = __ballot(ch);
-      if (ch) {
-        const int r = kc + __popcll(cm & ((1ull << lane) - 1ull));
-        if (r < MAXW) { s_chl[r] = j; s_ctok[r] = tk; }
-      }
-      kc += __popcll(cm);
     }
     rank = wave_max_i(rank);
     if (ks > MAXW || kc > MAXW) {
