@@ -843,6 +843,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_ring_kernel(AttnParams p) {
       else {
 #pragma unroll
         for (int i = 0; i < VW; ++i) load_vfrag(vf[i], ST, i);
+        // left to itself the scheduler sinks every V read to just in front of its MFMA (fewer live registers) and
+        // the second half of the step then waits out one LDS round trip per pair of MFMAs
+        __builtin_amdgcn_sched_barrier(0);
       }
       score_kt(kf[kt & 1], kt);
       if (kt < 3) probs_kt(kt + 1);
@@ -860,6 +863,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_ring_kernel(AttnParams p) {
 #pragma unroll
       for (int n = 0; n < NQ; ++n) ot[n][i >> 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[i % VW].f.v, pf[n][i & 1].v, ot[n][i >> 1], 0, 0, 0);
       if (i + VW < NVS) load_vfrag(vf[i % VW], ST, i + VW);
+      __builtin_amdgcn_sched_barrier(0);   // keeps the read of step i + VW here, VW steps ahead of its use
     }
   };
 
