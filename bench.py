@@ -35,27 +35,27 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # traffic null.
 FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
 MEASURED_TRAFFIC_KIB = {
-    ("stress_1024px", "accept"): (17635.8, 192.6),
-    ("stress_1024px", "attn"): (293569.8, 18432.0),
-    ("stress_1024px", "lmhead"): (799965.8, 262144.0),
+    ("stress_1024px", "accept"): (17650.3, 193.1),
+    ("stress_1024px", "attn"): (293568.2, 18432.0),
+    ("stress_1024px", "lmhead"): (796679.5, 262144.0),
     ("stress_1024px", "pack_h"): (13974.7, 27927.3),
-    ("stress_1024px", "row_stats"): (131200.0, 99.9),
+    ("stress_1024px", "row_stats"): (131200.7, 99.1),
     ("stress_1024px", "select"): (588.3, 0.9),
-    ("janus_batched", "accept"): (7515.2, 83.9),
-    ("janus_batched", "attn"): (49804.0, 8118.4),
-    ("janus_batched", "lmhead"): (98406.1, 28864.0),
+    ("janus_batched", "accept"): (7529.7, 83.9),
+    ("janus_batched", "attn"): (49791.0, 8118.1),
+    ("janus_batched", "lmhead"): (98439.2, 28864.0),
     ("janus_batched", "pack_h"): (5026.5, 10984.7),
     ("janus_batched", "row_stats"): (14509.0, 42.3),
     ("janus_batched", "select"): (424.0, 1.4),
-    ("janus_pro_7b", "accept"): (974.7, 11.2),
+    ("janus_pro_7b", "accept"): (989.2, 11.2),
     ("janus_pro_7b", "attn"): (6521.0, 1080.0),
-    ("janus_pro_7b", "lmhead"): (70022.8, 3840.0),
+    ("janus_pro_7b", "lmhead"): (70016.7, 3840.0),
     ("janus_pro_7b", "pack_h"): (1969.6, 3979.6),
     ("janus_pro_7b", "row_stats"): (1997.0, 5.6),
     ("janus_pro_7b", "select"): (52.8, 0.2),
-    ("lumina_mgpt_7b_768", "accept"): (983.3, 11.2),
+    ("lumina_mgpt_7b_768", "accept"): (997.8, 11.2),
     ("lumina_mgpt_7b_768", "attn"): (22158.7, 1080.0),
-    ("lumina_mgpt_7b_768", "lmhead"): (270005.0, 15360.0),
+    ("lumina_mgpt_7b_768", "lmhead"): (269860.2, 15360.0),
     ("lumina_mgpt_7b_768", "pack_h"): (6437.9, 12916.4),
     ("lumina_mgpt_7b_768", "row_stats"): (7806.1, 5.6),
     ("lumina_mgpt_7b_768", "select"): (144.2, 0.2),
