@@ -224,18 +224,22 @@ def tau_sweep(args) -> int:
 KERNEL_NAMES = {0: "attn", 1: "attn_merge", 2: "lmhead", 3: "row_stats", 4: "accept", 5: "select", 8: "pack_h"}
 
 
-def measure_workload(index: int, steps: int, warmup: int, args, hbm_meas: float, mfma_meas: float):
+def measure_workload(index: int, steps: int, warmup: int, args, hbm_meas: float, mfma_meas: float, cfg_mix: str = None):
     """Times `steps` whole steps of one configuration (wall clock), then the same steps again with the
     library's per-kernel events on; returns (inputs, device step, dict for the JSON line)."""
     import torch
     from paper_2605_07230_amd import binding, workloads as wl
     inp = wl.make_config(index, args.seed)
     ds = binding.DeviceStep(inp)
+    cfg_mix = cfg_mix or args.cfg_mix
     copies = max(1, args.copies)
     # weights are repacked once into MFMA operand order, as at model load (outside the timed region)
     packed = inp.dtype == "bf16" and not args.row_major_w
     layout = binding.W_PACKED32 if packed else binding.W_ROWMAJOR
     w0 = ds.pack_w() if packed else ds.w
+    # guidance mixed into the hidden rows (one product over n_nodes rows) or into the logits (two products)
+    premix = packed and inp.h_uncond is not None and cfg_mix == "hidden"
+    ds.cfg_mix = binding.CFG_MIX_HIDDEN if premix else binding.CFG_MIX_LOGITS
     ws = [w0] + [w0.clone() for _ in range(copies - 1)]
     kcs = [ds.k_cache] + [ds.k_cache.clone() for _ in range(copies - 1)]
     vcs = [ds.v_cache] + [ds.v_cache.clone() for _ in range(copies - 1)]
@@ -285,16 +289,16 @@ def measure_workload(index: int, steps: int, warmup: int, args, hbm_meas: float,
             kernel_us[name] = ms * 1e3 / n
     ds.ctx.set_kernel_timing(False)
 
-    rows = inp.n_nodes * (2 if inp.h_uncond is not None else 1)
+    rows = inp.n_nodes * (2 if (inp.h_uncond is not None and not premix) else 1)   # rows the projection multiplies
     tiled = packed and rows >= 512 and inp.vocab % 256 == 0
     # projection: bound by the matrix cores when the step has several hundred rows, by the W stream otherwise
     if tiled:
-        flops = algorithmic_flops_lmhead(inp)
+        flops = 2 * rows * inp.hidden * inp.vocab      # executed: with the hidden-row mix half of the two-product count
         ach = flops / (kernel_us["lmhead"] * 1e-6) / 1e12
         roof_lm = {"kernel": "lmhead_bf16_tiled_kernel", "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
                    "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(inp.name, "lmhead"),
-                   "algorithmic_flops": flops, "algorithmic_bytes": algorithmic_bytes_lmhead(inp),
-                   "frac_of_measured_peak": ach / mfma_meas}
+                   "algorithmic_flops": flops, "flops_two_products": algorithmic_flops_lmhead(inp),
+                   "algorithmic_bytes": algorithmic_bytes_lmhead(inp), "frac_of_measured_peak": ach / mfma_meas}
     else:
         nbytes = algorithmic_bytes_lmhead(inp)
         ach = nbytes / (kernel_us["lmhead"] * 1e-6) / 1e9
@@ -345,7 +349,8 @@ def measure_workload(index: int, steps: int, warmup: int, args, hbm_meas: float,
         "config": {"workload": inp.name, "rows": inp.n_rows, "prompts": inp.n_prompts, "tree_nodes": inp.n_nodes,
                    "prefix_len": int(inp.prefix_len.max()), "heads": inp.n_heads, "head_dim": inp.head_dim,
                    "hidden": inp.hidden, "vocab": inp.vocab, "cfg_scale": inp.cfg_scale, "top_k": inp.top_k,
-                   "input_copies_rotated": copies, "lmhead_w_layout": "packed32" if packed else "row_major"},
+                   "input_copies_rotated": copies, "lmhead_w_layout": "packed32" if packed else "row_major",
+                   "cfg_mix": "hidden_rows" if premix else ("logits" if inp.h_uncond is not None else "none")},
     }
     del ws, kcs, vcs
     return inp, ds, out, packed
@@ -361,6 +366,9 @@ def main() -> int:
     ap.add_argument("--other-steps", type=int, default=200)
     ap.add_argument("--copies", type=int, default=4, help="independent copies of W / KV rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cfg-mix", choices=["hidden", "logits"], default="hidden",
+                    help="where the guidance mix is taken: on the hidden rows (one product, default) or on the logits (two products)")
+    ap.add_argument("--no-two-products", action="store_true", help="skip the second timing of the headline workload with the mix on the logits")
     ap.add_argument("--no-vendor-gemm", action="store_true", help="skip the vendor GEMM timed beside the tiled projection")
     ap.add_argument("--row-major-w", action="store_true", help="keep the LM-head matrix row-major (default: packed once, as at model load)")
     ap.add_argument("--cache-warm", action="store_true", help="also time the steps on one copy of the inputs (served from the last-level cache)")
@@ -468,14 +476,25 @@ def main() -> int:
                     "ms_per_step_synchronous": lr_sync.seconds * 1e3 / max(lr_sync.steps, 1)}
         del loop
 
+    # the same workload with the guidance mix on the logits (two products), for comparison
+    two_products = None
+    if head["config"]["cfg_mix"] == "hidden_rows" and not args.no_two_products:
+        print("[bench] headline workload, guidance mix on the logits", file=sys.stderr, flush=True)
+        _, ds2, h2, _ = measure_workload(args.workload, min(args.steps, 100), min(args.warmup, 10), args, hbm_meas, mfma_meas, cfg_mix="logits")
+        two_products = {"ms_per_step": h2["ms_per_step"], "steps_per_s": h2["steps_per_s"], "kernel_us": h2["kernel_us"], "roofline": h2["roofline"]}
+        ds2.ctx.close()
+        del ds2
+        torch.cuda.empty_cache()
+
     # yardstick for the tiled projection: the vendor GEMM (torch.matmul, bf16 result) on the same
     # rows x hidden x vocab product, W rotated over two copies; it has no guidance combine and writes half
     # the bytes.  Context only: no part of the step calls it.
     vendor = None
     if head["roofline"]["bound"] == "mfma" and not args.no_vendor_gemm:
         try:
-            rows_v = inp.n_nodes * (2 if inp.h_uncond is not None else 1)
-            a_v = torch.cat([ds.h_cond, ds.h_uncond]) if ds.h_uncond is not None else ds.h_cond   # the step's own rows
+            two = ds.h_uncond is not None and head["config"]["cfg_mix"] != "hidden_rows"
+            rows_v = inp.n_nodes * (2 if two else 1)                       # as many rows as the projection multiplies
+            a_v = torch.cat([ds.h_cond, ds.h_uncond]) if two else ds.h_cond   # the step's own rows
             w_v = [ds.w.t(), ds.w.clone().t()]
             for i in range(4):
                 c_v = a_v @ w_v[i % 2]
@@ -526,6 +545,7 @@ def main() -> int:
         "kv_commit": commit,
         "convergence_weights": weights,
         "decode_loop": loop_out,
+        "guidance_mix_on_logits": two_products,
         "vendor_gemm_yardstick": vendor,
         "roofline": head["roofline"],
         "roofline_attention": head["roofline_attention"],

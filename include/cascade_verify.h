@@ -205,8 +205,19 @@ int tree_verify_attn_static(void* hip_stream, const tree_attn_args* args, int32_
  * consecutive over the hidden dimension.  A wavefront then streams the matrix as contiguous
  * 1 KiB operand loads.  Same bytes, same values: results do not depend on the layout beyond
  * float32 summation order.
+ *
+ * Where the guidance mix is taken.  The projection is linear and has no bias, so
+ *     l_u + s (l_c - l_u) = (h_u + s (h_c - h_u)) W^T :
+ * CASCADE_CFG_MIX_LOGITS (0, the formula as written above) runs both products and mixes in the
+ * projection's epilogue; CASCADE_CFG_MIX_HIDDEN mixes the two hidden rows of a node first (float32,
+ * in the order u + s (c - u), rounded once to bf16) and runs ONE product over n_nodes rows - half
+ * the multiplications.  The only difference is that one rounding of the mixed row: about 2^-9
+ * relative per element, which shows in g as an error of a few 1e-3 of the row's largest |g| at
+ * guidance scale 5 (inside the 2e-2 this library's bf16 results are held to).  Honoured for bf16
+ * with CASCADE_W_PACKED32; every other case runs the two products.
  */
 typedef enum { CASCADE_W_ROWMAJOR = 0, CASCADE_W_PACKED32 = 1 } cascade_w_layout;
+typedef enum { CASCADE_CFG_MIX_LOGITS = 0, CASCADE_CFG_MIX_HIDDEN = 1 } cascade_cfg_mix;
 /* Enqueues the repacking of a bf16 [vocab, hidden] matrix (DEVICE) into w_packed (DEVICE, same
  * byte size, must not alias w).  vocab % 64 == 0, hidden % 128 == 0. */
 int cascade_pack_lmhead_w(cascade_ctx* ctx, const void* w, int32_t vocab, int32_t hidden, void* w_packed);
@@ -220,6 +231,7 @@ typedef struct {
   cascade_w_layout w_layout;
   float cfg_scale, temperature;
   int32_t top_k;
+  cascade_cfg_mix cfg_mix;    /* where the guidance mix is taken (see above); 0 = on the logits */
   float* logits;
   float *row_max, *row_thr, *row_lse;
 } lmhead_args;

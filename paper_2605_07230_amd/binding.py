@@ -21,6 +21,7 @@ WALK_SEQUENTIAL, WALK_LONGEST = 0, 1
 FEATURES_HIDDEN, FEATURES_LOGITS = 0, 1
 K_ATTN, K_ATTN_MERGE, K_LMHEAD, K_ROW_STATS, K_ACCEPT, K_SELECT = range(6)
 W_ROWMAJOR, W_PACKED32 = 0, 1
+CFG_MIX_LOGITS, CFG_MIX_HIDDEN = 0, 1
 OK, EINVAL, ESHAPE, EDTYPE, ENOMEM, EHIP, ETREE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ["cascade_create", "cascade_destroy", "cascade_strerror", "cascade_device_status", "cascade_workspace_bytes",
@@ -46,7 +47,7 @@ class tree_attn_args(C.Structure):
 class lmhead_args(C.Structure):
     _fields_ = [("dtype", C.c_int), ("n_nodes", _i32), ("hidden", _i32), ("vocab", _i32), ("h_cond", _vp),
                 ("h_uncond", _vp), ("w", _vp), ("w_layout", C.c_int), ("cfg_scale", _f32), ("temperature", _f32), ("top_k", _i32),
-                ("logits", _vp), ("row_max", _vp), ("row_thr", _vp), ("row_lse", _vp)]
+                ("cfg_mix", C.c_int), ("logits", _vp), ("row_max", _vp), ("row_thr", _vp), ("row_lse", _vp)]
 
 
 class accept_args(C.Structure):
@@ -243,10 +244,11 @@ def cascade_pack_lmhead_w(ctx: Context, w: torch.Tensor) -> torch.Tensor:
 
 
 def lmhead_softmax_cfg(ctx: Context, *, h_cond, h_uncond, w, cfg_scale, temperature, top_k, logits, row_max, row_thr, row_lse,
-                       w_layout: int = W_ROWMAJOR) -> None:
+                       w_layout: int = W_ROWMAJOR, cfg_mix: int = CFG_MIX_LOGITS) -> None:
     a = lmhead_args()
     a.dtype = _dtype_code(w)
     a.w_layout = w_layout
+    a.cfg_mix = cfg_mix
     a.n_nodes, a.hidden, a.vocab = h_cond.shape[0], h_cond.shape[1], w.shape[0]
     a.h_cond, a.h_uncond, a.w = _ptr(h_cond), _ptr(h_uncond), _ptr(w)
     a.cfg_scale, a.temperature, a.top_k = cfg_scale, temperature, top_k
@@ -322,6 +324,7 @@ class DeviceStep:
     def __init__(self, inp, device="cuda:0", stream: Optional[torch.cuda.Stream] = None, max_tree: Optional[int] = None):
         """max_tree overrides the bound on nodes per tree handed to the library (default: the largest tree)."""
         self.inp = inp
+        self.cfg_mix = CFG_MIX_LOGITS     # where lmhead() takes the guidance mix (CFG_MIX_HIDDEN: one product over mixed rows)
         dev = torch.device(device)
         dt = torch.bfloat16 if inp.dtype == "bf16" else torch.float32
 
@@ -374,7 +377,8 @@ class DeviceStep:
             w_layout = W_PACKED32 if self.w_packed is not None else W_ROWMAJOR
         lmhead_softmax_cfg(self.ctx, h_cond=self.h_cond, h_uncond=self.h_uncond, w=w, w_layout=w_layout or W_ROWMAJOR,
                            cfg_scale=self.inp.cfg_scale, temperature=self.inp.temperature, top_k=self.inp.top_k,
-                           logits=self.logits, row_max=self.row_max, row_thr=self.row_thr, row_lse=self.row_lse)
+                           logits=self.logits, row_max=self.row_max, row_thr=self.row_thr, row_lse=self.row_lse,
+                           cfg_mix=self.cfg_mix)
 
     def accept(self, tau_pos=None, tau_seq=None, feature_space=FEATURES_HIDDEN):
         cascade_accept(self.ctx, feature_space=feature_space, node_off=self.node_off, parent=self.parent, token=self.token, h_cond=self.h_cond,

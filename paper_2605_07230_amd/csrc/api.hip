@@ -271,6 +271,7 @@ int lmhead_softmax_cfg(cascade_ctx* ctx, const lmhead_args* a) {
   if (a->n_nodes > L.max_nodes_total || a->hidden > L.hidden || a->vocab > L.vocab || a->vocab > CASCADE_MAX_VOCAB)
     return CASCADE_ESHAPE;
   if (a->w_layout != CASCADE_W_ROWMAJOR && a->w_layout != CASCADE_W_PACKED32) return CASCADE_EINVAL;
+  if (a->cfg_mix != CASCADE_CFG_MIX_LOGITS && a->cfg_mix != CASCADE_CFG_MIX_HIDDEN) return CASCADE_EINVAL;
   if (a->dtype == CASCADE_BF16) {
     if ((a->hidden % 128) || (a->vocab % 64)) return CASCADE_ESHAPE;
   } else {

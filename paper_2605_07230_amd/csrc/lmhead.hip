@@ -179,6 +179,34 @@ __global__ __launch_bounds__(256) void pack32_kernel(const uint16_t* __restrict_
   dst[((int64_t)rb * (K / 16) + ks) * 64 + lane] = v;
 }
 
+// The same operand order for the guidance-mixed rows u + s (c - u) (float32, rounded once to bf16): the
+// projection is linear, so one product over these rows gives the mixed logits.
+__global__ __launch_bounds__(256) void pack32_mix_kernel(const uint16_t* __restrict__ src_c, const uint16_t* __restrict__ src_u,
+                                                          uint4* __restrict__ dst, int rows, int K, float s) {
+  const int lane = threadIdx.x & 63, r32 = lane & 31, half = lane >> 5;
+  const int ks = blockIdx.x * 4 + (threadIdx.x >> 6), rb = blockIdx.y;
+  if (ks >= K / 16) return;
+  const int row = 32 * rb + r32;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row < rows) {
+    const int64_t o = (int64_t)row * K + 16 * ks + 8 * half;
+    const uint4 c = *(const uint4*)(src_c + o), u = *(const uint4*)(src_u + o);
+    const uint32_t cw[4] = {c.x, c.y, c.z, c.w}, uw[4] = {u.x, u.y, u.z, u.w};
+    uint32_t m[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float c0 = __uint_as_float(cw[i] << 16), c1 = __uint_as_float(cw[i] & 0xffff0000u);
+      const float u0 = __uint_as_float(uw[i] << 16), u1 = __uint_as_float(uw[i] & 0xffff0000u);
+      typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+      typedef float f2 __attribute__((ext_vector_type(2)));
+      const b2 r = __builtin_convertvector(f2{u0 + s * (c0 - u0), u1 + s * (c1 - u1)}, b2);   // round to nearest even
+      m[i] = *(const uint32_t*)&r;
+    }
+    v = make_uint4(m[0], m[1], m[2], m[3]);
+  }
+  dst[((int64_t)rb * (K / 16) + ks) * 64 + lane] = v;
+}
+
 // NSTEPS > 0: k16 steps per wave known at compile time (K = 64 * NSTEPS), deep fully unrolled pipeline.
 template <bool CFG, int NSTEPS>
 __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
@@ -337,8 +365,13 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
 //     (bare: a fenced barrier would wait for every outstanding load);
 //   - step 1 is multiplied while the first fragments of h + 1 are read.
 // The barrier sits before the last step's multiplications, which cover it.
-template <bool CFG>
+// HALF (no guidance only): 128-row tiles for steps whose 256-row tiles would leave compute units idle - a wave owns
+// 2 x 2 accumulators, waves w and w + 4 request the same H block (same bytes to the same LDS slot), so that the
+// loader and its wait counts are the same code.
+template <bool CFG, bool HALF>
 __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int n_mtiles) {
+  static_assert(!(CFG && HALF), "half tiles exist for the plain projection only");
+  constexpr int NI = HALF ? 2 : 4;   // row blocks per wave
   extern __shared__ u32x4 lds[];     // [4 half-stages][2 k16 steps][16 blocks: 8 H then 8 W][64 lanes]
   constexpr int NBUF = 4, HS = 2, HBYTES = HS * 16 * 1024;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -360,6 +393,7 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
     int64_t rb;   // 32-row block index in the source matrix
     if (b4 == 0) {
       if (CFG) { base = (const char*)(wave < 4 ? p.hp_cond : p.hp_uncond); rb = (int64_t)mt * 4 + (wave & 3); }
+      else if (HALF) { base = (const char*)p.hp_cond; rb = (int64_t)mt * 4 + (wave & 3); }
       else { base = (const char*)p.hp_cond; rb = (int64_t)mt * 8 + wave; }
     } else {
       base = (const char*)p.w;
@@ -374,7 +408,8 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
   // each lane's 16 bytes land at 16 * lane behind it.
   auto request = [&](int h, int buf, int i) {
     const char* g = src[i & 1] + ((int64_t)min(h, last) * HS + (i >> 1)) * 1024;
-    const unsigned l = lds0 + buf * HBYTES + ((i >> 1) * 16 + wave + 8 * (i & 1)) * 1024;
+    const int slot = (i & 1) ? 8 + wave : (HALF ? (wave & 3) : wave);
+    const unsigned l = lds0 + buf * HBYTES + ((i >> 1) * 16 + slot) * 1024;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(lane_off), "s"(g) : "memory");
   };
   // A wave's own loads of the next half-stage have landed when at most the 2 x 4 later ones are
@@ -388,32 +423,32 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
   const int wm = wave >> 2, wn = wave & 3;
   // row blocks of wave row wm: with guidance 2 wm, 2 wm + 1 (conditional) and the same two of the
   // unconditional half (+4); without, 4 wm .. 4 wm + 3
-  const unsigned a_base = 1024u * (CFG ? 2 * wm : 4 * wm) + lane_off, b_base = 1024u * (8 + 2 * wn) + lane_off;
+  const unsigned a_base = 1024u * ((CFG || HALF) ? 2 * wm : 4 * wm) + lane_off, b_base = 1024u * (8 + 2 * wn) + lane_off;
   const unsigned a_off[2] = {opaque(a_base), opaque(a_base + 65536u)};
   const unsigned b_off[2] = {opaque(b_base), opaque(b_base + 65536u)};
 
-  f32x16 acc[4][2];
+  f32x16 acc[NI][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < NI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  Frag8 fa[2][4], fb[2][2];   // operand fragments, double-buffered by k16 step
-  auto read_one = [&](int slot, int buf, int ks, int idx) {   // idx 0-3: H fragment, 4-5: W fragment
+  Frag8 fa[2][NI], fb[2][2];   // operand fragments, double-buffered by k16 step
+  auto read_one = [&](int slot, int buf, int ks, int idx) {   // idx 0 .. NI-1: H fragment, NI, NI+1: W fragment
     const int byte0 = buf * HBYTES + ks * 16 * 1024;          // compile-time after unrolling
-    if (idx < 4) {
+    if (idx < NI) {
       const int rel = CFG ? (idx & 1) + 4 * (idx >> 1) : idx;
       fa[slot][idx].n = *(const u32x4*)(lds_b + a_off[byte0 >> 16] + ((byte0 & 65535) + rel * 1024));
     } else {
-      fb[slot][idx - 4].n = *(const u32x4*)(lds_b + b_off[byte0 >> 16] + ((byte0 & 65535) + (idx - 4) * 1024));
+      fb[slot][idx - NI].n = *(const u32x4*)(lds_b + b_off[byte0 >> 16] + ((byte0 & 65535) + (idx - NI) * 1024));
     }
   };
-  // eight multiplications; after the k-th one, side(k) issues its piece of the other work
+  // 2 NI multiplications; after the k-th one, side(k) issues its piece of the other work
   auto multiply_with = [&](int slot, auto&& side) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
+    for (int k = 0; k < 2 * NI; ++k) {
       __builtin_amdgcn_sched_barrier(0);
       acc[k >> 1][k & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][k >> 1].v, fb[slot][k & 1].v, acc[k >> 1][k & 1], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
@@ -421,7 +456,8 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  constexpr int FRAG_ORDER[6] = {0, 4, 5, 1, 2, 3};   // the order in which the multiplications first need them
+  constexpr int NFR = NI + 2;                          // fragments per k16 step
+  constexpr int FRAG_ORDER[6] = {0, NI, NI + 1, 1, 2, 3};   // the order in which the multiplications first need them
 
 #pragma unroll
   for (int h = 0; h < NBUF - 1; ++h)
@@ -429,17 +465,18 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
     for (int i = 0; i < 4; ++i) request(h, h, i);
   land_and_sync();
 #pragma unroll
-  for (int k = 0; k < 6; ++k) read_one(0, 0, 0, FRAG_ORDER[k]);
+  for (int k = 0; k < NFR; ++k) read_one(0, 0, 0, FRAG_ORDER[k]);
   for (int h0 = 0; h0 < n_half; h0 += NBUF) {   // hidden is a multiple of 128: four half-stages always divide it
 #pragma unroll
     for (int b = 0; b < NBUF; ++b) {
       const int hn = h0 + b + NBUF - 1, bn = (b + NBUF - 1) % NBUF;
       multiply_with(0, [&](int k) {
-        if (k < 6) read_one(1, b, 1, FRAG_ORDER[k]);
+        if (HALF) { read_one(1, b, 1, FRAG_ORDER[k]); request(hn, bn, k); }   // four multiplications: a read and a request behind each
+        else if (k < 6) read_one(1, b, 1, FRAG_ORDER[k]);
         else { request(hn, bn, 2 * (k - 6)); request(hn, bn, 2 * (k - 6) + 1); }
       });
       land_and_sync();
-      multiply_with(1, [&](int k) { if (k < 6) read_one(0, (b + 1) % NBUF, 0, FRAG_ORDER[k]); });
+      multiply_with(1, [&](int k) { if (k < NFR) read_one(0, (b + 1) % NBUF, 0, FRAG_ORDER[k]); });
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the clamped extra requests must not outlive the workgroup's LDS
@@ -447,8 +484,8 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
   // epilogue: accumulator (i, j), register r of lane (r32, half) is row 8 (r / 4) + 4 half + r % 4, column r32
   const int v0 = nt * 256 + 64 * wn;
 #pragma unroll
-  for (int i = 0; i < (CFG ? 2 : 4); ++i) {
-    const int node0 = CFG ? mt * 128 + 32 * (2 * wm + i) : mt * 256 + 32 * (4 * wm + i);
+  for (int i = 0; i < (CFG ? 2 : NI); ++i) {
+    const int node0 = (CFG || HALF) ? mt * 128 + 32 * (2 * wm + i) : mt * 256 + 32 * (4 * wm + i);
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -821,12 +858,16 @@ hipError_t launch_bf16_gemm(cascade_ctx* ctx, const LmParams& p, int grid) {
 hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
   LmParams p = make_params(a);
   const int grid = (a->vocab / 64) * p.n_mchunks;
-  const bool cfg = a->h_uncond != nullptr;
+  // guidance mixed into the hidden rows while they are packed: from here on a plain projection of n_nodes rows
+  const bool premix = a->h_uncond != nullptr && a->cfg_mix == CASCADE_CFG_MIX_HIDDEN && a->w_layout == CASCADE_W_PACKED32;
+  const bool cfg = a->h_uncond != nullptr && !premix;
   if (a->w_layout == CASCADE_W_PACKED32) {
     // many rows and a vocabulary made of whole 256-column tiles: LDS-tiled kernel, 256-row tiles
     const int rows = a->n_nodes * (cfg ? 2 : 1);
-    const bool tiled = rows >= 512 && (a->vocab % 256) == 0;
-    const int nodes_per_tile = cfg ? 128 : 256;
+    const bool tiled = rows >= (cfg ? 512 : 257) && (a->vocab % 256) == 0;
+    // plain projection: 128-row tiles when the 256-row tiling would leave compute units without a workgroup
+    const bool half = !cfg && (long)((a->n_nodes + 255) / 256) * (a->vocab / 256) < ctx->n_cu;
+    const int nodes_per_tile = (cfg || half) ? 128 : 256;
     const int n_mtiles = (a->n_nodes + nodes_per_tile - 1) / nodes_per_tile;
     // repack this step's hidden states into operand order (zero rows up to a whole tile / chunk)
     const int rblocks = tiled ? n_mtiles * (nodes_per_tile / 32) : p.n_mchunks * 2;
@@ -837,8 +878,13 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
     dim3 pgrid((a->hidden / 16 + 3) / 4, rblocks, cfg ? 2 : 1);
     {
       KernelTimer t(ctx, CASCADE_K_PACK);
-      CASCADE_TIMED_LAUNCH(t, pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_cond, hc,
-                           (const uint16_t*)a->h_uncond, hu, a->n_nodes, a->hidden);
+      if (premix) {
+        CASCADE_TIMED_LAUNCH(t, pack32_mix_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_cond,
+                             (const uint16_t*)a->h_uncond, hc, a->n_nodes, a->hidden, a->cfg_scale);
+      } else {
+        CASCADE_TIMED_LAUNCH(t, pack32_kernel, pgrid, dim3(256), 0, ctx->stream, (const uint16_t*)a->h_cond, hc,
+                             (const uint16_t*)a->h_uncond, hu, a->n_nodes, a->hidden);
+      }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -846,12 +892,13 @@ hipError_t launch_lmhead_bf16(cascade_ctx* ctx, const lmhead_args* a) {
     p.hp_uncond = hu;
     if (tiled) {
       const size_t smem = (size_t)4 * 32 * 1024;   // ring of four 32 KiB half-stages
-      static bool attr_done[2] = {false, false};
-      auto kern = cfg ? lmhead_bf16_tiled_kernel<true> : lmhead_bf16_tiled_kernel<false>;
-      if (!attr_done[cfg]) {
+      static bool attr_done[3] = {false, false, false};
+      auto kern = cfg ? lmhead_bf16_tiled_kernel<true, false> : (half ? lmhead_bf16_tiled_kernel<false, true> : lmhead_bf16_tiled_kernel<false, false>);
+      const int which = cfg ? 0 : (half ? 1 : 2);
+      if (!attr_done[which]) {
         e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        attr_done[cfg] = true;
+        attr_done[which] = true;
       }
       KernelTimer t(ctx, CASCADE_K_LMHEAD);
       CASCADE_TIMED_LAUNCH(t, kern, dim3((a->vocab / 256) * n_mtiles), dim3(512), smem, ctx->stream, p, n_mtiles);
