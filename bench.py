@@ -35,29 +35,29 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # traffic null.
 FETCH_FACTOR, WRITE_FACTOR = 2.0, 1.0
 MEASURED_TRAFFIC_KIB = {
-    ("stress_1024px", "accept"): (17650.3, 193.1),
+    ("stress_1024px", "accept"): (17650.3, 193.0),
     ("stress_1024px", "attn"): (293568.2, 18432.0),
-    ("stress_1024px", "lmhead"): (796679.5, 262144.0),
-    ("stress_1024px", "pack_h"): (13974.7, 27927.3),
-    ("stress_1024px", "row_stats"): (131200.7, 99.1),
+    ("stress_1024px", "lmhead"): (393828.6, 262144.0),
+    ("stress_1024px", "pack_h"): (8196.5, 8192.0),
+    ("stress_1024px", "row_stats"): (131197.7, 98.2),
     ("stress_1024px", "select"): (588.3, 0.9),
     ("janus_batched", "accept"): (7529.7, 83.9),
-    ("janus_batched", "attn"): (49791.0, 8118.1),
-    ("janus_batched", "lmhead"): (98439.2, 28864.0),
-    ("janus_batched", "pack_h"): (5026.5, 10984.7),
-    ("janus_batched", "row_stats"): (14509.0, 42.3),
+    ("janus_batched", "attn"): (49841.0, 8118.3),
+    ("janus_batched", "lmhead"): (82011.0, 28864.0),
+    ("janus_batched", "pack_h"): (3612.5, 4096.0),
+    ("janus_batched", "row_stats"): (14507.5, 42.3),
     ("janus_batched", "select"): (424.0, 1.4),
     ("janus_pro_7b", "accept"): (989.2, 11.2),
     ("janus_pro_7b", "attn"): (6521.0, 1080.0),
-    ("janus_pro_7b", "lmhead"): (70016.7, 3840.0),
-    ("janus_pro_7b", "pack_h"): (1969.6, 3979.6),
-    ("janus_pro_7b", "row_stats"): (1997.0, 5.6),
+    ("janus_pro_7b", "lmhead"): (67752.2, 3840.0),
+    ("janus_pro_7b", "pack_h"): (484.5, 512.0),
+    ("janus_pro_7b", "row_stats"): (1995.8, 5.6),
     ("janus_pro_7b", "select"): (52.8, 0.2),
     ("lumina_mgpt_7b_768", "accept"): (997.8, 11.2),
     ("lumina_mgpt_7b_768", "attn"): (22158.7, 1080.0),
-    ("lumina_mgpt_7b_768", "lmhead"): (269860.2, 15360.0),
-    ("lumina_mgpt_7b_768", "pack_h"): (6437.9, 12916.4),
-    ("lumina_mgpt_7b_768", "row_stats"): (7806.1, 5.6),
+    ("lumina_mgpt_7b_768", "lmhead"): (264994.3, 15360.0),
+    ("lumina_mgpt_7b_768", "pack_h"): (484.5, 512.0),
+    ("lumina_mgpt_7b_768", "row_stats"): (7804.2, 5.6),
     ("lumina_mgpt_7b_768", "select"): (144.2, 0.2),
 }
 
@@ -139,6 +139,7 @@ def tau_sweep(args) -> int:
         if w0 is None:
             w0 = inp.w
         ds = binding.DeviceStep(inp)
+        ds.cfg_mix = binding.CFG_MIX_HIDDEN if args.cfg_mix == "hidden" else binding.CFG_MIX_LOGITS
         if w_packed is None:
             w_packed = ds.pack_w()
         ds.lmhead(w_packed, binding.W_PACKED32)
@@ -190,6 +191,7 @@ def tau_sweep(args) -> int:
     # walk) of the full stress configuration (4200-key prefixes), timed per threshold on rotating input copies
     inp = wl.make_config(4, 0, w=w0)
     ds = binding.DeviceStep(inp)
+    ds.cfg_mix = binding.CFG_MIX_HIDDEN if args.cfg_mix == "hidden" else binding.CFG_MIX_LOGITS
     kcs = [ds.k_cache] + [ds.k_cache.clone() for _ in range(3)]
     vcs = [ds.v_cache] + [ds.v_cache.clone() for _ in range(3)]
     ws = [w_packed] + [w_packed.clone() for _ in range(3)]
@@ -210,7 +212,7 @@ def tau_sweep(args) -> int:
         torch.cuda.synchronize()
         step_us[t] = (time.perf_counter() - t0) * 1e6 / 40
     assert ds.ctx.device_status() == binding.OK
-    out = {"metric": "tau_sweep", "tokens": "rank-zipf of the parent's logits" if args.rank_zipf else "generator's tokens",
+    out = {"metric": "tau_sweep", "cfg_mix": "hidden_rows" if args.cfg_mix == "hidden" else "logits", "tokens": "rank-zipf of the parent's logits" if args.rank_zipf else "generator's tokens",
            "workload": "stress_1024px trees (prefix cut to 64), seeds 0..%d; whole-step time on the full configuration" % (args.sweep_seeds - 1),
            "per_tau": {str(t): {"mean_accept_len": float(np.mean(acc_len[t])), "accept_us": float(np.mean(acc_us[t])),
                                 "select_us": float(np.mean(sel_us[t])), "prompts": len(acc_len[t]),
