@@ -292,7 +292,8 @@ def measure_workload(index: int, steps: int, warmup: int, args, hbm_meas: float,
     ds.ctx.set_kernel_timing(False)
 
     rows = inp.n_nodes * (2 if (inp.h_uncond is not None and not premix) else 1)   # rows the projection multiplies
-    tiled = packed and rows >= 512 and inp.vocab % 256 == 0
+    guidance_pairs = inp.h_uncond is not None and not premix
+    tiled = packed and rows >= (512 if guidance_pairs else 257) and inp.vocab % 256 == 0   # the library's own rule
     # projection: bound by the matrix cores when the step has several hundred rows, by the W stream otherwise
     if tiled:
         flops = 2 * rows * inp.hidden * inp.vocab      # executed: with the hidden-row mix half of the two-product count
@@ -464,11 +465,11 @@ def main() -> int:
         pool = [inp] + [wl.make_config(args.workload, args.seed + 1 + i) for i in range(3)]
         for p_ in pool[1:]:
             p_.w = inp.w
-        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed)
+        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed, cfg_mix=binding.CFG_MIX_HIDDEN if args.cfg_mix == "hidden" else binding.CFG_MIX_LOGITS)
         loop.run(max_steps=5)                           # warm-up
-        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed)
+        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed, cfg_mix=binding.CFG_MIX_HIDDEN if args.cfg_mix == "hidden" else binding.CFG_MIX_LOGITS)
         lr_sync = loop.run()                            # one stream wait per step
-        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed)
+        loop = decode.DecodeLoop(pool, args.decode_image, packed_w=packed, cfg_mix=binding.CFG_MIX_HIDDEN if args.cfg_mix == "hidden" else binding.CFG_MIX_LOGITS)
         lr = loop.run_pipelined()                       # accepted lengths read back two steps late
         assert lr.accept_lens == lr_sync.accept_lens and lr.emitted == lr_sync.emitted
         loop_out = {"image_tokens": args.decode_image, "steps": lr.steps, "tokens": lr.tokens,

@@ -46,7 +46,8 @@ class DecodeLoop:
     LAG = 2          # steps the host's knowledge of the accepted lengths may trail the device
     RING = 4         # pinned read-back slots (> LAG)
 
-    def __init__(self, pool, image_tokens: int, device: str = "cuda:0", packed_w: bool = True):
+    def __init__(self, pool, image_tokens: int, device: str = "cuda:0", packed_w: bool = True,
+                 cfg_mix: int = binding.CFG_MIX_LOGITS):
         first = pool[0]
         if any(p.n_prompts != 1 for p in pool):
             raise ValueError("the decode loop drives one prompt")
@@ -66,6 +67,8 @@ class DecodeLoop:
         # (the pipelined loop runs up to LAG further steps before it learns that the image is complete)
         self.cap = -(-(P0 + image_tokens + (self.LAG + 1) * (self.max_depth + 1) + 1) // 8) * 8
         self.steps = [binding.DeviceStep(p, device) for p in pool]
+        for st in self.steps:
+            st.cfg_mix = cfg_mix           # where the projection takes the guidance mix (honoured for packed bf16 weights)
         self.ctx = binding.Context(max_rows=S, max_nodes_total=self.max_tree * S, max_nodes_per_tree=self.max_tree,
                                    max_prefix=self.cap, n_heads=first.n_heads, head_dim=first.head_dim,
                                    hidden=first.hidden, vocab=first.vocab)
