@@ -366,8 +366,8 @@ __global__ __launch_bounds__(256) void lmhead_bf16_packed_kernel(LmParams p) {
 //   - step 1 is multiplied while the first fragments of h + 1 are read.
 // The barrier sits before the last step's multiplications, which cover it.
 // HALF (no guidance only): 128-row tiles for steps whose 256-row tiles would leave compute units idle - a wave owns
-// 2 x 2 accumulators, waves w and w + 4 request the same H block (same bytes to the same LDS slot), so that the
-// loader and its wait counts are the same code.
+// 2 x 2 accumulators; the tile has four H blocks per k16 step, eight per half-stage: wave w requests block w % 4 of
+// step w / 4, so every wave issues three loads per half-stage (one H, two W) and the wait counts stay uniform.
 template <bool CFG, bool HALF>
 __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int n_mtiles) {
   static_assert(!(CFG && HALF), "half tiles exist for the plain projection only");
@@ -407,14 +407,19 @@ __global__ __launch_bounds__(512) void lmhead_bf16_tiled_kernel(LmParams p, int 
   // clamped, that data is never multiplied.  M0 carries the LDS address of the wave's 1 KiB block;
   // each lane's 16 bytes land at 16 * lane behind it.
   auto request = [&](int h, int buf, int i) {
-    const char* g = src[i & 1] + ((int64_t)min(h, last) * HS + (i >> 1)) * 1024;
+    if (HALF && i == 2) return;                                   // (i is a constant after unrolling)
+    const int ks = (HALF && i == 0) ? (wave >> 2) : (i >> 1);     // half tiles: the wave's one H block belongs to step wave / 4
+    const char* g = src[i & 1] + ((int64_t)min(h, last) * HS + ks) * 1024;
     const int slot = (i & 1) ? 8 + wave : (HALF ? (wave & 3) : wave);
-    const unsigned l = lds0 + buf * HBYTES + ((i >> 1) * 16 + slot) * 1024;
+    const unsigned l = lds0 + buf * HBYTES + (ks * 16 + slot) * 1024;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(lane_off), "s"(g) : "memory");
   };
   // A wave's own loads of the next half-stage have landed when at most the 2 x 4 later ones are
   // outstanding; its LDS reads are complete at lgkmcnt(0).
-  auto land_and_sync = [&]() { asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+  auto land_and_sync = [&]() {
+    if (HALF) asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // 2 x 3 later loads
+    else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  };
 
   // LDS read addresses: one base register per 64 KiB and role, the rest is an immediate.  The bases
   // are made opaque so that the compiler neither re-derives them nor keeps further sums alive.
