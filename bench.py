@@ -8,6 +8,12 @@ vocabulary 65536), the shape on which the roofline targets mean something: the p
 by the matrix cores, attention and the row statistics by HBM.  The smaller configurations are timed
 in the same run and reported as a nested block.
 
+Guidance: by default the mix is taken on the hidden rows (lmhead_args.cfg_mix = CASCADE_CFG_MIX_HIDDEN: the
+projection is linear, so one product over the mixed rows gives the mixed logits up to one bf16 rounding of those
+rows); `config.cfg_mix` says so, `roofline.algorithmic_flops` counts what that path executes, and the block
+`guidance_mix_on_logits` holds the same workload timed with the formula as written (two products).  `--cfg-mix logits`
+makes that the headline instead.  `vendor_gemm_yardstick` is torch.matmul on the projection's own shape, for context.
+
 The large read-only inputs (LM-head matrix, KV cache) are rotated over several independent copies
 so that consecutive steps cannot be served from the 256 MB Infinity Cache: in a real decode loop a
 whole model's weights stream between two verification steps.
