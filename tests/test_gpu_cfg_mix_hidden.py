@@ -69,6 +69,36 @@ def test_half_tiles_with_mixed_rows_every_logit(hidden, sizes):
     pu.check_accept_and_path(inp, ds, require_margin=False)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_tiled_projection_random_shapes_both_mixes(seed):
+    """Random row counts (257-700 nodes in 3-6 prompts), hidden sizes and vocabularies through both guidance
+    mixes: guidance-pair tiles, plain 256-row tiles and 128-row tiles with ragged last tiles; every logit compared."""
+    rng = np.random.default_rng(100 + seed)
+    n_prompts = int(rng.integers(3, 7))
+    total = int(rng.integers(257, 701))
+    cuts = np.sort(rng.choice(np.arange(1, total), size=n_prompts - 1, replace=False))
+    sizes = np.diff(np.concatenate([[0], cuts, [total]])).astype(int)
+    trees = [wl.grow_tree(rng, int(n), min(6, int(n) - 1), 8) if n > 1 else np.array([-1], np.int32) for n in sizes]
+    hidden = int(rng.choice([128, 256, 512, 896]))
+    vocab = int(rng.choice([256, 512, 768]))
+    scale = float(rng.choice([3.0, 5.0]))
+    inp = wl.make_inputs(seed=100 + seed, name="edge", dtype="bf16", n_prompts=n_prompts, cfg=True, n_heads=4, n_kv_heads=2,
+                         head_dim=64, hidden=hidden, vocab=vocab, prefix_lens=[int(x) for x in rng.integers(1, 40, size=2 * n_prompts)],
+                         trees=trees, cfg_scale=scale, temperature=1.0, top_k=int(rng.choice([0, 30])), tau_pos=0.9, tau_seq=0.9,
+                         eps_tvd=0.5, token_law="zipf")
+    print(f"[random tiled] nodes={inp.n_nodes} sizes={sizes.tolist()} hidden={hidden} vocab={vocab} scale={scale}", flush=True)
+    for mix in (binding.CFG_MIX_LOGITS, binding.CFG_MIX_HIDDEN):
+        ds = binding.DeviceStep(inp)
+        ds.pack_w()
+        ds.cfg_mix = mix
+        ds.lmhead()
+        torch.cuda.synchronize()
+        assert ds.ctx.device_status() == binding.OK
+        pu.check_lmhead(inp, ds)
+        if mix == binding.CFG_MIX_HIDDEN:
+            _check_single_product(inp, ds, np.arange(inp.n_nodes))
+
+
 def test_tiled_projection_with_mixed_rows_ragged_batch():
     inp = wl.make_config(3, 0)
     ds = _run(inp)
