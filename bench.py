@@ -47,9 +47,9 @@ MEASURED_TRAFFIC_KIB = {
     ("stress_1024px", "pack_h"): (8196.5, 8192.0),
     ("stress_1024px", "row_stats"): (131197.7, 98.2),
     ("stress_1024px", "select"): (588.3, 0.9),
-    ("janus_batched", "accept"): (7529.7, 83.9),
-    ("janus_batched", "attn"): (49841.0, 8118.3),
-    ("janus_batched", "lmhead"): (82011.0, 28864.0),
+    ("janus_batched", "accept"): (7529.7, 83.8),
+    ("janus_batched", "attn"): (49856.9, 8118.1),
+    ("janus_batched", "lmhead"): (82009.7, 28864.0),
     ("janus_batched", "pack_h"): (3612.5, 4096.0),
     ("janus_batched", "row_stats"): (14507.5, 42.3),
     ("janus_batched", "select"): (424.0, 1.4),
